@@ -1,0 +1,574 @@
+// Small kernels of the decode step: weight packing, row assembly + embedding gather, RMSNorm with fused
+// residual/split-K reduction, RoPE + K/V placement, SwiGLU, vocabulary argmax / Gumbel-max, verify/accept.
+// Also the fp32-mode GEMM and attention (plain ALU kernels used by the fp32 configuration).
+#include "tidar_internal.h"
+
+namespace {
+
+template <typename T> __device__ inline float to_f(T v);
+template <> __device__ inline float to_f<float>(float v) { return v; }
+template <> __device__ inline float to_f<bf16_t>(bf16_t v) { return (float)v; }
+template <typename T> __device__ inline T from_f(float v);
+template <> __device__ inline float from_f<float>(float v) { return v; }
+template <> __device__ inline bf16_t from_f<bf16_t>(float v) { return (bf16_t)v; }   // round to nearest even
+
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+__device__ inline float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+    return v;
+}
+
+// ------------------------------------------------------------------ weight packing
+// bf16: dst[((tile * (K/32) + q) * 64 + lane) * 8 + j] = src[(16 t + lane%16) * K + 32 q + 8 (lane/16) + j]
+__global__ void pack_bf16_kernel(const bf16_t *__restrict__ src, int rows, int K, bf16_t *__restrict__ dst,
+                                 int tile_off, int tile_stride) {
+    int ksteps = K / 32;
+    size_t n_frag = (size_t)(rows / 16) * ksteps * 64;          // one 16-byte fragment piece per index
+    for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < n_frag;
+         idx += (size_t)gridDim.x * blockDim.x) {
+        int lane = (int)(idx & 63);
+        size_t tq = idx >> 6;
+        int q = (int)(tq % ksteps);
+        int t = (int)(tq / ksteps);
+        const bf16_t *s = src + (size_t)(16 * t + (lane & 15)) * K + 32 * q + 8 * (lane >> 4);
+        size_t dt = (size_t)(tile_off + t * tile_stride);
+        bf16_t *o = dst + ((dt * ksteps + q) * 64 + lane) * 8;
+        *(bf16x8 *)o = *(const bf16x8 *)s;
+    }
+}
+
+// fp32: plain row-major; tile placement only.
+__global__ void pack_f32_kernel(const float *__restrict__ src, int rows, int K, float *__restrict__ dst,
+                                int tile_off, int tile_stride) {
+    size_t n = (size_t)rows * K;
+    for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < n; idx += (size_t)gridDim.x * blockDim.x) {
+        int r = (int)(idx / K);
+        int c = (int)(idx % K);
+        size_t dr = (size_t)(tile_off + (r / 16) * tile_stride) * 16 + (r % 16);
+        dst[dr * K + c] = src[idx];
+    }
+}
+
+// ------------------------------------------------------------------ row assembly + embedding gather (+ RoPE table)
+template <typename T>
+__global__ void embed_rows_kernel(const T *__restrict__ embed, const int32_t *__restrict__ tokens, int tok_stride,
+                                  const int32_t *__restrict__ prefix_len, RowDesc d, int d_model, int mask_id,
+                                  int hd, float rope_base, float *__restrict__ x, int32_t *__restrict__ pos_out,
+                                  float *__restrict__ rope_cs) {
+    int row = blockIdx.x;                 // b * R + r
+    int b = row / d.R;
+    int r = row - b * d.R;
+    int L = prefix_len[d.seq_base + b];
+    RowInfo ri = row_info(d, r, L);
+    int tok = (r < d.nc) ? tokens[(size_t)b * tok_stride + r] : mask_id;
+    if (threadIdx.x == 0) pos_out[row] = ri.pos;
+    const T *e = embed + (size_t)tok * d_model;
+    float *xo = x + (size_t)row * d_model;
+    for (int c = threadIdx.x; c < d_model; c += blockDim.x) xo[c] = to_f<T>(e[c]);
+    // cos/sin of pos * base^(-2i/hd), angle formed in double so that long contexts keep their phase
+    int half = hd / 2;
+    for (int i = threadIdx.x; i < half; i += blockDim.x) {
+        double inv = exp2(-(double)(2 * i) / (double)hd * log2((double)rope_base));
+        double ang = (double)ri.pos * inv;
+        double s, c;
+        sincos(ang, &s, &c);
+        rope_cs[((size_t)row * half + i) * 2 + 0] = (float)c;
+        rope_cs[((size_t)row * half + i) * 2 + 1] = (float)s;
+    }
+}
+
+// ------------------------------------------------------------------ residual add (split-K partials) + RMSNorm
+template <typename T>
+__global__ void rmsnorm_kernel(float *__restrict__ x, const float *__restrict__ part, int S, size_t part_stride,
+                               const T *__restrict__ gain, float eps, int R, int row0, int d_model,
+                               T *__restrict__ out) {
+    int Rh = R - row0;
+    int b = blockIdx.x / Rh;
+    int o = blockIdx.x - b * Rh;
+    size_t row = (size_t)b * R + row0 + o;
+    float *xr = x + row * d_model;
+    float ss = 0.f;
+    for (int c = threadIdx.x; c < d_model; c += blockDim.x) {
+        float v = xr[c];
+        for (int s = 0; s < S; ++s) v += part[(size_t)s * part_stride + row * d_model + c];
+        if (S > 0) xr[c] = v;
+        ss += v * v;
+    }
+    __shared__ float red[16];
+    ss = wave_sum(ss);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    float tot = 0.f;
+    for (int w = 0; w < (int)(blockDim.x >> 6); ++w) tot += red[w];
+    float rs = rsqrtf(tot / (float)d_model + eps);
+    T *orow = out + (size_t)blockIdx.x * d_model;
+    for (int c = threadIdx.x; c < d_model; c += blockDim.x) orow[c] = from_f<T>(xr[c] * rs * to_f<T>(gain[c]));
+}
+
+// ------------------------------------------------------------------ RoPE + K/V placement
+// One block per row.  qkv_part: [S][M][q_dim + 2 kv_dim] fp32.  Q rows -> q_out [M][q_dim];
+// K/V of causal rows -> cache at position L + r; K/V of mask rows -> scratch tiles
+// k_scr [B][n_kv][n_mtiles][16][hd], v_scr [B][n_kv][n_mtiles][hd][16].
+template <typename T>
+__global__ void rope_kv_kernel(const float *__restrict__ part, int S, size_t part_stride,
+                               const float *__restrict__ rope_cs, const int32_t *__restrict__ prefix_len, RowDesc d,
+                               int n_q, KvView kv, T *__restrict__ q_out, T *__restrict__ k_scr,
+                               T *__restrict__ v_scr) {
+    int row = blockIdx.x;
+    int b = row / d.R;
+    int r = row - b * d.R;
+    int hd = kv.hd, half = hd / 2, n_kv = kv.n_kv;
+    int q_dim = n_q * hd, kv_dim = n_kv * hd, width = q_dim + 2 * kv_dim;
+    const float *cs = rope_cs + (size_t)row * half * 2;
+    auto val = [&](int col) {
+        float v = 0.f;
+        for (int s = 0; s < S; ++s) v += part[(size_t)s * part_stride + (size_t)row * width + col];
+        return v;
+    };
+    // Q: rotate pairs (i, i + half)
+    for (int idx = threadIdx.x; idx < n_q * half; idx += blockDim.x) {
+        int h = idx / half, i = idx - h * half;
+        float a = val(h * hd + i), bb = val(h * hd + i + half);
+        float c = cs[2 * i], s = cs[2 * i + 1];
+        q_out[(size_t)row * q_dim + h * hd + i] = from_f<T>(a * c - bb * s);
+        q_out[(size_t)row * q_dim + h * hd + i + half] = from_f<T>(bb * c + a * s);
+    }
+    // destination of this row's K/V
+    bool causal = r < d.nc;
+    int L = prefix_len[d.seq_base + b];
+    int page = 0, slot = 0, mt = 0;
+    int n_mtiles = (d.nb * d.bl + 15) / 16;
+    if (causal) {
+        int p = L + r;
+        page = kv.page_table[(size_t)(d.seq_base + b) * kv.pages_per_seq + (p >> 4)];
+        slot = p & 15;
+    } else {
+        int m = r - d.nc;
+        mt = m >> 4;
+        slot = m & 15;
+    }
+    T *kp = (T *)kv.k_pages;
+    T *vp = (T *)kv.v_pages;
+    for (int idx = threadIdx.x; idx < n_kv * half; idx += blockDim.x) {
+        int h = idx / half, i = idx - h * half;
+        float a = val(q_dim + h * hd + i), bb = val(q_dim + h * hd + i + half);
+        float c = cs[2 * i], s = cs[2 * i + 1];
+        T k0 = from_f<T>(a * c - bb * s), k1 = from_f<T>(bb * c + a * s);
+        T v0 = from_f<T>(val(q_dim + kv_dim + h * hd + i)), v1 = from_f<T>(val(q_dim + kv_dim + h * hd + i + half));
+        if (causal) {
+            kp[k_page_offset(kv, page, h, slot, i)] = k0;
+            kp[k_page_offset(kv, page, h, slot, i + half)] = k1;
+            vp[v_page_offset(kv, page, h, slot, i)] = v0;
+            vp[v_page_offset(kv, page, h, slot, i + half)] = v1;
+        } else {
+            size_t tile = ((size_t)b * n_kv + h) * n_mtiles + mt;
+            k_scr[(tile * 16 + slot) * hd + i] = k0;
+            k_scr[(tile * 16 + slot) * hd + i + half] = k1;
+            v_scr[(tile * hd + i) * 16 + slot] = v0;
+            v_scr[(tile * hd + i + half) * 16 + slot] = v1;
+        }
+    }
+}
+
+// K/V given directly (attention entry point): same placement, no rotation.
+template <typename T>
+__global__ void place_kv_kernel(const T *__restrict__ k_new, const T *__restrict__ v_new,
+                                const int32_t *__restrict__ prefix_len, RowDesc d, KvView kv, T *__restrict__ k_scr,
+                                T *__restrict__ v_scr) {
+    int row = blockIdx.x;
+    int b = row / d.R;
+    int r = row - b * d.R;
+    int hd = kv.hd, n_kv = kv.n_kv;
+    bool causal = r < d.nc;
+    int L = prefix_len[d.seq_base + b];
+    int page = 0, slot = 0, mt = 0;
+    int n_mtiles = (d.nb * d.bl + 15) / 16;
+    if (causal) {
+        int p = L + r;
+        page = kv.page_table[(size_t)(d.seq_base + b) * kv.pages_per_seq + (p >> 4)];
+        slot = p & 15;
+    } else {
+        int m = r - d.nc;
+        mt = m >> 4;
+        slot = m & 15;
+    }
+    T *kp = (T *)kv.k_pages;
+    T *vp = (T *)kv.v_pages;
+    for (int idx = threadIdx.x; idx < n_kv * hd; idx += blockDim.x) {
+        int h = idx / hd, i = idx - h * hd;
+        T kk = k_new[(size_t)row * n_kv * hd + idx], vv = v_new[(size_t)row * n_kv * hd + idx];
+        if (causal) {
+            kp[k_page_offset(kv, page, h, slot, i)] = kk;
+            vp[v_page_offset(kv, page, h, slot, i)] = vv;
+        } else {
+            size_t tile = ((size_t)b * n_kv + h) * n_mtiles + mt;
+            k_scr[(tile * 16 + slot) * hd + i] = kk;
+            v_scr[(tile * hd + i) * 16 + slot] = vv;
+        }
+    }
+}
+
+// ------------------------------------------------------------------ SwiGLU over interleaved gate/up columns
+template <typename T>
+__global__ void swiglu_kernel(const float *__restrict__ part, int S, size_t part_stride, int M, int d_ff,
+                              T *__restrict__ out) {
+    size_t n = (size_t)M * d_ff;
+    for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < n; idx += (size_t)gridDim.x * blockDim.x) {
+        size_t row = idx / d_ff;
+        int f = (int)(idx - row * d_ff);
+        size_t gcol = (size_t)32 * (f >> 4) + (f & 15);
+        size_t base = row * (size_t)(2 * d_ff) + gcol;
+        float g = 0.f, u = 0.f;
+        for (int s = 0; s < S; ++s) {
+            g += part[(size_t)s * part_stride + base];
+            u += part[(size_t)s * part_stride + base + 16];
+        }
+        float act = g / (1.f + __expf(-g));
+        out[idx] = from_f<T>(act * u);
+    }
+}
+
+// ------------------------------------------------------------------ vocabulary argmax / Gumbel-max
+// Counter-based noise keyed by (seed, sequence, predicted absolute position, token id): a splitmix-style
+// finaliser over a linear combination of the key fields; 24 bits -> u in (0,1) -> -ln(-ln u).
+__device__ inline uint32_t hash_u24(uint64_t key, uint32_t v) {
+    uint64_t z = key + (uint64_t)(v + 1) * 0xD6E8FEB86659FD93ull;
+    z ^= z >> 30;
+    z *= 0xBF58476D1CE4E5B9ull;
+    z ^= z >> 27;
+    z *= 0x94D049BB133111EBull;
+    z ^= z >> 31;
+    return (uint32_t)(z >> 40);
+}
+
+__global__ void argmax_rows_kernel(const float *__restrict__ logits, int Rh, int vocab, int n_choose,
+                                   const int32_t *__restrict__ pos_rows, int pos_stride, int pos_row0, int seq_base,
+                                   int sample, float temperature, uint64_t seed, float beta, int mix_base,
+                                   int mix_stride, int32_t *__restrict__ y) {
+    int row = blockIdx.x;                  // b * Rh + o
+    int b = row / Rh;
+    int o = row - b * Rh;
+    const float *lg = logits + (size_t)row * vocab;
+    bool choose = o < n_choose;            // a row whose token is *taken* (causal logits)
+    const float *mix = nullptr;
+    if (choose && beta != 1.0f) mix = logits + ((size_t)b * Rh + mix_base + (size_t)o * mix_stride) * vocab;
+    bool noisy = choose && sample;
+    uint64_t key = 0;
+    float inv_t = 1.f;
+    if (noisy) {
+        int pos_pred = pos_rows[(size_t)b * pos_stride + pos_row0 + o] + 1;      // causal rows are label shifted
+        key = seed ^ (0x9E3779B97F4A7C15ull * (uint64_t)(pos_pred + 1)) ^
+              (0xC2B2AE3D27D4EB4Full * (uint64_t)(seq_base + b + 1));
+        inv_t = 1.f / temperature;
+    }
+    float best = -INFINITY;
+    int best_i = 0x7fffffff;
+    for (int v = threadIdx.x; v < vocab; v += blockDim.x) {
+        float val = lg[v];
+        if (mix) val = beta * val + (1.f - beta) * mix[v];
+        if (noisy) {
+            float u = ((float)hash_u24(key, (uint32_t)v) + 0.5f) * (1.0f / 16777216.0f);
+            val = val * inv_t + (-logf(-logf(u)));
+        }
+        if (val > best || (val == best && v < best_i)) { best = val; best_i = v; }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        float ob = __shfl_xor(best, off);
+        int oi = __shfl_xor(best_i, off);
+        if (ob > best || (ob == best && oi < best_i)) { best = ob; best_i = oi; }
+    }
+    __shared__ float sb[16];
+    __shared__ int si[16];
+    if ((threadIdx.x & 63) == 0) { sb[threadIdx.x >> 6] = best; si[threadIdx.x >> 6] = best_i; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < (int)(blockDim.x >> 6); ++w)
+            if (sb[w] > best || (sb[w] == best && si[w] < best_i)) { best = sb[w]; best_i = si[w]; }
+        y[row] = best_i;
+    }
+}
+
+// ------------------------------------------------------------------ verify / accept / commit / next-draft select
+// y: [B][k(k+1)] chosen token per row (rows: c_0..c_{k-1}, blk_0[0..k), ...).  One thread per sequence.
+__global__ void verify_step_kernel(const int32_t *__restrict__ y, const int32_t *__restrict__ drafts, int k, int B,
+                                   int32_t *__restrict__ prefix_len, int32_t *__restrict__ accepted_len,
+                                   int32_t *__restrict__ accepted_tokens, int32_t *__restrict__ next_drafts) {
+    int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    int R = k * (k + 1);
+    const int32_t *yb = y + (size_t)b * R;
+    int32_t c[TIDAR_MAX_K];
+    for (int i = 0; i < k; ++i) c[i] = drafts[(size_t)b * k + i];
+    int a = 1;                                              // c_0 is final already
+    while (a < k && c[a] == yb[a - 1]) ++a;                 // causal row a-1 judges draft a
+    accepted_len[b] = a;
+    for (int i = 0; i < k; ++i) accepted_tokens[(size_t)b * k + i] = (i < a) ? c[i] : -1;
+    next_drafts[(size_t)b * k] = yb[a - 1];                 // token at the first unverified position
+    for (int s = 1; s < k; ++s) next_drafts[(size_t)b * k + s] = yb[k + (a - 1) * k + s];
+    prefix_len[b] += a;                                     // commit: rejected drafts' K/V fall behind the frontier
+}
+
+__global__ void finish_ar_kernel(const int32_t *__restrict__ y, int B, int32_t *__restrict__ prefix_len,
+                                 int32_t *__restrict__ token_out) {
+    int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    token_out[b] = y[b];
+    prefix_len[b] += 1;
+}
+
+__global__ void finish_prefill_kernel(const int32_t *__restrict__ y, int k, int seq, int add_len, int last,
+                                      int32_t *__restrict__ prefix_len, int32_t *__restrict__ first_drafts) {
+    if (threadIdx.x == 0) prefix_len[seq] += add_len;
+    if (last && threadIdx.x < k) {
+        // y rows: last prompt row, then mask slots 0..k-1; slot 0 of the block is superseded by the causal token
+        first_drafts[(size_t)seq * k + threadIdx.x] = (threadIdx.x == 0) ? y[0] : y[1 + threadIdx.x];
+    }
+}
+
+__global__ void sum_partials_kernel(const float *__restrict__ part, int S, size_t stride, float *__restrict__ out) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < stride; i += (size_t)gridDim.x * blockDim.x) {
+        float v = 0.f;
+        for (int s = 0; s < S; ++s) v += part[(size_t)s * stride + i];
+        out[i] = v;
+    }
+}
+
+__global__ void set_i32_kernel(int32_t *p, int n, int32_t v) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+// ------------------------------------------------------------------ fp32 GEMM (plain ALU): out[M][N] = a[M][K] w[N][K]^T
+__global__ __launch_bounds__(256) void gemm_f32_kernel(const float *__restrict__ a, const float *__restrict__ w,
+                                                       float *__restrict__ out, int M, int N, int K) {
+    __shared__ float As[16][33];
+    __shared__ float Ws[64][33];
+    int n0 = blockIdx.x * 64, m0 = blockIdx.y * 16;
+    int tc = threadIdx.x & 63, tr = threadIdx.x >> 6;      // column, row group (4 rows each)
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int k0 = 0; k0 < K; k0 += 32) {
+        for (int i = threadIdx.x; i < 16 * 32; i += 256) {
+            int r = i >> 5, c = i & 31;
+            As[r][c] = (m0 + r < M && k0 + c < K) ? a[(size_t)(m0 + r) * K + k0 + c] : 0.f;
+        }
+        for (int i = threadIdx.x; i < 64 * 32; i += 256) {
+            int r = i >> 5, c = i & 31;
+            Ws[r][c] = (n0 + r < N && k0 + c < K) ? w[(size_t)(n0 + r) * K + k0 + c] : 0.f;
+        }
+        __syncthreads();
+#pragma unroll 8
+        for (int c = 0; c < 32; ++c) {
+            float wv = Ws[tc][c];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc[i] = fmaf(As[tr * 4 + i][c], wv, acc[i]);
+        }
+        __syncthreads();
+    }
+    for (int i = 0; i < 4; ++i) {
+        int m = m0 + tr * 4 + i;
+        if (m < M && n0 + tc < N) out[(size_t)m * N + n0 + tc] = acc[i];
+    }
+}
+
+// ------------------------------------------------------------------ fp32 hybrid-mask attention (plain ALU)
+// One wave per (sequence, query head, row).  Keys: cache positions [0, L + nc) then the mask rows' scratch tiles.
+__global__ __launch_bounds__(64) void attention_f32_kernel(const float *__restrict__ q, KvView kv,
+                                                           const float *__restrict__ k_scr,
+                                                           const float *__restrict__ v_scr,
+                                                           const int32_t *__restrict__ prefix_len, RowDesc d, int n_q,
+                                                           float *__restrict__ out) {
+    int row = blockIdx.x;                  // b * R + r
+    int head = blockIdx.y;
+    int b = row / d.R, r = row - b * d.R;
+    int hd = kv.hd, n_kv = kv.n_kv;
+    int g = head / (n_q / n_kv);
+    int L = prefix_len[d.seq_base + b];
+    RowInfo ri = row_info(d, r, L);
+    int n_cache = L + d.nc, n_mask = d.nb * d.bl, n_mtiles = (n_mask + 15) / 16;
+    int T = n_cache + n_mask;
+    const float *kp = (const float *)kv.k_pages;
+    const float *vp = (const float *)kv.v_pages;
+    const int32_t *pt = kv.page_table + (size_t)(d.seq_base + b) * kv.pages_per_seq;
+    __shared__ float qs[128];
+    __shared__ float ps[64];
+    int lane = threadIdx.x;
+    for (int i = lane; i < hd; i += 64) qs[i] = q[((size_t)row * n_q + head) * hd + i];
+    __syncthreads();
+    float scale = rsqrtf((float)hd);
+    float m_run = -INFINITY, l_run = 0.f;
+    float o0 = 0.f, o1 = 0.f;              // this lane's output dims: lane, lane + 64
+    for (int t0 = 0; t0 < T; t0 += 64) {
+        int t = t0 + lane;
+        bool vis = false;
+        const float *krow = nullptr;
+        if (t < n_cache) {
+            vis = (t < L) || (t - L < ri.vis);
+            krow = kp + k_page_offset(kv, pt[t >> 4], g, t & 15, 0);
+        } else if (t < T) {
+            int m = t - n_cache;
+            vis = (ri.blk >= 0) && (m / d.bl == ri.blk);
+            krow = k_scr + ((((size_t)b * n_kv + g) * n_mtiles + (m >> 4)) * 16 + (m & 15)) * hd;
+        }
+        float s = -INFINITY;
+        if (vis) {
+            float acc = 0.f;
+            for (int i = 0; i < hd; ++i) acc = fmaf(qs[i], krow[i], acc);
+            s = acc * scale;
+        }
+        float mx = wave_max(s);
+        if (mx == -INFINITY) continue;     // nothing visible in this chunk (uniform across the wave)
+        float m_new = fmaxf(m_run, mx);
+        float alpha = __expf(m_run - m_new);
+        float p = vis ? __expf(s - m_new) : 0.f;
+        l_run = l_run * alpha + wave_sum(p);
+        o0 *= alpha;
+        o1 *= alpha;
+        m_run = m_new;
+        ps[lane] = p;
+        __syncthreads();
+        int lim = min(64, T - t0);
+        for (int j = 0; j < lim; ++j) {
+            float pj = ps[j];
+            if (pj == 0.f) continue;
+            int tj = t0 + j;
+            const float *vbase;
+            size_t stride_d;
+            if (tj < n_cache) {
+                vbase = vp + v_page_offset(kv, pt[tj >> 4], g, tj & 15, 0);
+                stride_d = 16;
+            } else {
+                int m = tj - n_cache;
+                vbase = v_scr + (((size_t)b * n_kv + g) * n_mtiles + (m >> 4)) * hd * 16 + (m & 15);
+                stride_d = 16;
+            }
+            if (lane < hd) o0 = fmaf(pj, vbase[(size_t)lane * stride_d], o0);
+            if (lane + 64 < hd) o1 = fmaf(pj, vbase[(size_t)(lane + 64) * stride_d], o1);
+        }
+        __syncthreads();
+    }
+    float inv = 1.f / l_run;
+    if (lane < hd) out[((size_t)row * n_q + head) * hd + lane] = o0 * inv;
+    if (lane + 64 < hd) out[((size_t)row * n_q + head) * hd + lane + 64] = o1 * inv;
+}
+
+inline int grid_for(size_t n, int block, int cap = 4096) {
+    size_t g = (n + block - 1) / block;
+    return (int)(g < 1 ? 1 : (g > (size_t)cap ? cap : g));
+}
+
+}  // namespace
+
+void launch_pack_weight(int dtype, const void *src, int rows, int cols, void *dst, int tile_off, int tile_stride,
+                        hipStream_t st) {
+    if (dtype == TIDAR_BF16) {
+        size_t n = (size_t)(rows / 16) * (cols / 32) * 64;
+        pack_bf16_kernel<<<grid_for(n, 256, 65536), 256, 0, st>>>((const bf16_t *)src, rows, cols, (bf16_t *)dst,
+                                                                   tile_off, tile_stride);
+    } else {
+        size_t n = (size_t)rows * cols;
+        pack_f32_kernel<<<grid_for(n, 256, 65536), 256, 0, st>>>((const float *)src, rows, cols, (float *)dst,
+                                                                  tile_off, tile_stride);
+    }
+}
+
+void launch_embed_rows(int dtype, const void *embed, const int32_t *tokens, int tok_stride, const int32_t *prefix_len,
+                       RowDesc d, int B, int d_model, int mask_id, int hd, float rope_base, float *x,
+                       int32_t *pos_out, float *rope_cs, hipStream_t st) {
+    int rows = B * d.R;
+    if (dtype == TIDAR_BF16)
+        embed_rows_kernel<bf16_t><<<rows, 256, 0, st>>>((const bf16_t *)embed, tokens, tok_stride, prefix_len, d,
+                                                         d_model, mask_id, hd, rope_base, x, pos_out, rope_cs);
+    else
+        embed_rows_kernel<float><<<rows, 256, 0, st>>>((const float *)embed, tokens, tok_stride, prefix_len, d,
+                                                        d_model, mask_id, hd, rope_base, x, pos_out, rope_cs);
+}
+
+void launch_rmsnorm(int dtype, float *x, const float *part, int S, size_t part_stride, const void *gain, float eps,
+                    int B, int R, int row0, int d_model, void *out, hipStream_t st) {
+    int rows = B * (R - row0);
+    if (dtype == TIDAR_BF16)
+        rmsnorm_kernel<bf16_t><<<rows, 256, 0, st>>>(x, part, S, part_stride, (const bf16_t *)gain, eps, R, row0,
+                                                      d_model, (bf16_t *)out);
+    else
+        rmsnorm_kernel<float><<<rows, 256, 0, st>>>(x, part, S, part_stride, (const float *)gain, eps, R, row0,
+                                                     d_model, (float *)out);
+}
+
+void launch_gemm_f32(const float *a, const float *w, float *out, int M, int N, int K, hipStream_t st) {
+    dim3 grid((N + 63) / 64, (M + 15) / 16);
+    gemm_f32_kernel<<<grid, 256, 0, st>>>(a, w, out, M, N, K);
+}
+
+void launch_rope_kv(int dtype, const float *qkv_part, int S, size_t part_stride, const float *rope_cs,
+                    const int32_t *prefix_len, RowDesc d, int B, int n_q, KvView kv, void *q_out, void *k_scr,
+                    void *v_scr, hipStream_t st) {
+    int rows = B * d.R;
+    if (dtype == TIDAR_BF16)
+        rope_kv_kernel<bf16_t><<<rows, 256, 0, st>>>(qkv_part, S, part_stride, rope_cs, prefix_len, d, n_q, kv,
+                                                      (bf16_t *)q_out, (bf16_t *)k_scr, (bf16_t *)v_scr);
+    else
+        rope_kv_kernel<float><<<rows, 256, 0, st>>>(qkv_part, S, part_stride, rope_cs, prefix_len, d, n_q, kv,
+                                                     (float *)q_out, (float *)k_scr, (float *)v_scr);
+}
+
+void launch_place_kv(int dtype, const void *k_new, const void *v_new, const int32_t *prefix_len, RowDesc d, int B,
+                     KvView kv, void *k_scr, void *v_scr, hipStream_t st) {
+    int rows = B * d.R;
+    if (dtype == TIDAR_BF16)
+        place_kv_kernel<bf16_t><<<rows, 256, 0, st>>>((const bf16_t *)k_new, (const bf16_t *)v_new, prefix_len, d, kv,
+                                                       (bf16_t *)k_scr, (bf16_t *)v_scr);
+    else
+        place_kv_kernel<float><<<rows, 256, 0, st>>>((const float *)k_new, (const float *)v_new, prefix_len, d, kv,
+                                                      (float *)k_scr, (float *)v_scr);
+}
+
+void launch_attention_f32(const float *q, KvView kv, const float *k_scr, const float *v_scr,
+                          const int32_t *prefix_len, RowDesc d, int B, int n_q, float *out, hipStream_t st) {
+    dim3 grid(B * d.R, n_q);
+    attention_f32_kernel<<<grid, 64, 0, st>>>(q, kv, k_scr, v_scr, prefix_len, d, n_q, out);
+}
+
+void launch_swiglu(int dtype, const float *part, int S, size_t part_stride, int M, int d_ff, void *out,
+                   hipStream_t st) {
+    size_t n = (size_t)M * d_ff;
+    if (dtype == TIDAR_BF16)
+        swiglu_kernel<bf16_t><<<grid_for(n, 256, 8192), 256, 0, st>>>(part, S, part_stride, M, d_ff, (bf16_t *)out);
+    else
+        swiglu_kernel<float><<<grid_for(n, 256, 8192), 256, 0, st>>>(part, S, part_stride, M, d_ff, (float *)out);
+}
+
+void launch_argmax_rows(const float *logits, int B, int Rh, int vocab, int n_choose, const int32_t *pos_rows,
+                        int pos_stride, int pos_row0, int seq_base, int sample, float temperature, uint64_t seed,
+                        float beta, int mix_base, int mix_stride, int32_t *y, hipStream_t st) {
+    argmax_rows_kernel<<<B * Rh, 1024, 0, st>>>(logits, Rh, vocab, n_choose, pos_rows, pos_stride, pos_row0, seq_base,
+                                                sample, temperature, seed, beta, mix_base, mix_stride, y);
+}
+
+void launch_verify_step(const int32_t *y, const int32_t *drafts, int k, int B, int32_t *prefix_len,
+                        int32_t *accepted_len, int32_t *accepted_tokens, int32_t *next_drafts, hipStream_t st) {
+    verify_step_kernel<<<(B + 63) / 64, 64, 0, st>>>(y, drafts, k, B, prefix_len, accepted_len, accepted_tokens,
+                                                     next_drafts);
+}
+
+void launch_finish_ar(const int32_t *y, int B, int32_t *prefix_len, int32_t *token_out, hipStream_t st) {
+    finish_ar_kernel<<<(B + 63) / 64, 64, 0, st>>>(y, B, prefix_len, token_out);
+}
+
+void launch_finish_prefill(const int32_t *y, int k, int seq, int add_len, int last, int32_t *prefix_len,
+                           int32_t *first_drafts, hipStream_t st) {
+    finish_prefill_kernel<<<1, 64, 0, st>>>(y, k, seq, add_len, last, prefix_len, first_drafts);
+}
+
+void launch_set_i32(int32_t *p, int n, int32_t v, hipStream_t st) {
+    set_i32_kernel<<<(n + 255) / 256, 256, 0, st>>>(p, n, v);
+}
+
+void launch_sum_partials(const float *part, int S, size_t stride, float *out, hipStream_t st) {
+    sum_partials_kernel<<<grid_for(stride, 256, 8192), 256, 0, st>>>(part, S, stride, out);
+}

@@ -1,0 +1,130 @@
+// Internal declarations shared by the library's translation units (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "tidar.h"
+
+typedef __bf16 bf16_t;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+// Row structure of one forward, identical for every sequence of the batch.
+// Rows per sequence: nc causal rows, then nb blocks of bl mask rows.
+// Block j is conditioned on the first cond0 + j causal rows.
+struct RowDesc {
+    int nc, nb, bl, cond0;
+    int R;          // nc + nb * bl
+    int seq_base;   // first sequence index (into prefix_len / page_table rows)
+};
+
+struct RowInfo {
+    int pos;   // absolute position id
+    int vis;   // number of new causal keys this row may see
+    int blk;   // mask block index, -1 for causal rows
+};
+
+__host__ __device__ inline RowInfo row_info(const RowDesc &d, int r, int L) {
+    RowInfo ri;
+    if (r < d.nc) {
+        ri.pos = L + r;
+        ri.vis = r + 1;
+        ri.blk = -1;
+    } else {
+        int m = r - d.nc;
+        int j = m / d.bl;
+        int s = m - j * d.bl;
+        ri.pos = L + d.cond0 + j + s;
+        ri.vis = d.cond0 + j;
+        ri.blk = j;
+    }
+    return ri;
+}
+
+// Paged cache geometry of one layer.
+struct KvView {
+    void *k_pages;             // layer base
+    void *v_pages;             // layer base
+    const int32_t *page_table;
+    int pages_per_seq;
+    int n_kv, hd;
+};
+
+__device__ inline size_t k_page_offset(const KvView &kv, int page, int h, int slot, int d) {
+    return (((size_t)page * kv.n_kv + h) * 16 + slot) * kv.hd + d;
+}
+__device__ inline size_t v_page_offset(const KvView &kv, int page, int h, int slot, int d) {
+    return (((size_t)page * kv.n_kv + h) * kv.hd + d) * 16 + slot;
+}
+
+// Profiling hooks (defined in tidar_lib.hip).
+enum KernelClass {
+    KC_EMBED = 0, KC_RMSNORM, KC_GEMM, KC_ROPE_KV, KC_ATTN, KC_ATTN_COMBINE, KC_SWIGLU, KC_ARGMAX, KC_VERIFY,
+    KC_PACK, KC_PLACE_KV, KC_COUNT
+};
+
+struct GemmPlan {
+    int mt;        // 16-row tiles per workgroup pass
+    int nt;        // 16-column tiles per wave
+    int splits;    // split-K factor
+    int bk;        // K elements staged per LDS chunk
+    int m_chunks;  // passes over M (grid.z)
+};
+
+GemmPlan plan_gemm_bf16(int M, int N, int K, bool force_single_split);
+
+// ---- launchers (each enqueues on `st`, checks nothing: callers validated shapes) ----
+void launch_pack_weight(int dtype, const void *src, int rows, int cols, void *dst, int tile_off, int tile_stride,
+                        hipStream_t st);
+
+void launch_embed_rows(int dtype, const void *embed, const int32_t *tokens, int tok_stride, const int32_t *prefix_len,
+                       RowDesc d, int B, int d_model, int mask_id, int hd, float rope_base,
+                       float *x, int32_t *pos_out, float *rope_cs, hipStream_t st);
+
+// x[row] += sum_s part[s][row]; out[row'] = rmsnorm(x[row]) * gain, rows [row0, R) of each sequence.
+void launch_rmsnorm(int dtype, float *x, const float *part, int S, size_t part_stride, const void *gain, float eps,
+                    int B, int R, int row0, int d_model, void *out, hipStream_t st);
+
+void launch_gemm_bf16(const bf16_t *a, const bf16_t *w_packed, float *out, int M, int N, int K, const GemmPlan &p,
+                      hipStream_t st);
+void launch_gemm_f32(const float *a, const float *w, float *out, int M, int N, int K, hipStream_t st);
+
+void launch_rope_kv(int dtype, const float *qkv_part, int S, size_t part_stride, const float *rope_cs,
+                    const int32_t *prefix_len, RowDesc d, int B, int n_q, KvView kv,
+                    void *q_out, void *k_scr, void *v_scr, hipStream_t st);
+
+void launch_place_kv(int dtype, const void *k_new, const void *v_new, const int32_t *prefix_len, RowDesc d, int B,
+                     KvView kv, void *k_scr, void *v_scr, hipStream_t st);
+
+struct AttnPlan {
+    int splits;
+    int n_chunks;        // q-tile chunks per kv head
+    int tiles_per_chunk;
+};
+AttnPlan plan_attention(int B, int n_kv, int group, int R, int max_keys);
+size_t attn_partial_floats(int B, int n_kv, int group, int R, int hd, int splits);
+
+void launch_attention_bf16(const bf16_t *q, KvView kv, const bf16_t *k_scr, const bf16_t *v_scr,
+                           const int32_t *prefix_len, RowDesc d, int B, int n_q, const AttnPlan &p, float *part,
+                           hipStream_t st);
+void launch_attention_combine(const float *part, int B, int R, int n_q, int n_kv, int hd, int splits, bf16_t *out,
+                              hipStream_t st);
+void launch_attention_f32(const float *q, KvView kv, const float *k_scr, const float *v_scr,
+                          const int32_t *prefix_len, RowDesc d, int B, int n_q, float *out, hipStream_t st);
+
+void launch_swiglu(int dtype, const float *part, int S, size_t part_stride, int M, int d_ff, void *out, hipStream_t st);
+
+// y[row] = argmax over vocab of (logits or, for the first n_choose rows of each sequence, the sampled /
+// beta-mixed value).  Rows per sequence Rh; causal row i mixes with row mix_base + i*mix_stride when beta != 1.
+void launch_argmax_rows(const float *logits, int B, int Rh, int vocab, int n_choose, const int32_t *pos_rows,
+                        int pos_stride, int pos_row0, int seq_base, int sample, float temperature, uint64_t seed,
+                        float beta, int mix_base, int mix_stride, int32_t *y, hipStream_t st);
+
+void launch_verify_step(const int32_t *y, const int32_t *drafts, int k, int B, int32_t *prefix_len,
+                        int32_t *accepted_len, int32_t *accepted_tokens, int32_t *next_drafts, hipStream_t st);
+void launch_finish_ar(const int32_t *y, int B, int32_t *prefix_len, int32_t *token_out, hipStream_t st);
+void launch_finish_prefill(const int32_t *y, int k, int seq, int add_len, int last, int32_t *prefix_len,
+                           int32_t *first_drafts, hipStream_t st);
+void launch_set_i32(int32_t *p, int n, int32_t v, hipStream_t st);
+void launch_sum_partials(const float *part, int S, size_t stride, float *out, hipStream_t st);

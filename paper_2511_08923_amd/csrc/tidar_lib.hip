@@ -1,0 +1,623 @@
+// Host side of the C ABI: argument validation, workspace carving, and the launch sequence of one forward.
+// Nothing here synchronises the device; every kernel goes onto the caller's stream in program order.
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "tidar_internal.h"
+
+namespace {
+
+const char *kClassNames[KC_COUNT] = {"embed_rows", "rmsnorm", "gemm", "rope_kv", "attention", "attention_combine",
+                                     "swiglu", "argmax_rows", "verify", "pack_weight", "place_kv"};
+
+struct ProfEvent {
+    int cls;
+    hipEvent_t start, stop;
+};
+
+}  // namespace
+
+struct tidar_ctx {
+    tidar_config cfg;
+    bool profiling;
+    std::vector<ProfEvent> events;
+    double ms[KC_COUNT];
+    int64_t launches[KC_COUNT];
+};
+
+namespace {
+
+constexpr int kPrefillChunk = 256;   // causal rows per prefill pass; with k <= 16 mask rows it fits 17 row tiles
+
+struct Prof {
+    tidar_ctx *ctx;
+    int cls;
+    hipStream_t st;
+    ProfEvent ev;
+    bool on;
+    Prof(tidar_ctx *c, int cls_, hipStream_t s) : ctx(c), cls(cls_), st(s), on(c && c->profiling) {
+        if (on) {
+            ev.cls = cls;
+            on = hipEventCreate(&ev.start) == hipSuccess && hipEventCreate(&ev.stop) == hipSuccess;
+            if (on) (void)hipEventRecord(ev.start, st);
+        }
+    }
+    ~Prof() {
+        if (on) {
+            (void)hipEventRecord(ev.stop, st);
+            ctx->events.push_back(ev);
+        }
+    }
+};
+
+inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
+inline size_t esize(int dtype) { return dtype == TIDAR_BF16 ? 2 : 4; }
+
+struct Layout {
+    size_t pos, rope_cs, x, xn, gemm_out, q, k_scr, v_scr, attn_part, o, h, xh, logits, y, total;
+    int attn_splits;
+};
+
+size_t gemm_out_floats(const tidar_config &c, int M, int N, int K) {
+    if (c.dtype != TIDAR_BF16) return (size_t)M * N;
+    // the split count depends on the row-tile class of M; taking the maximum over the class boundaries
+    // below M keeps the size monotone in M
+    const int bounds[5] = {16, 32, 80, 144, M};
+    size_t best = 0;
+    for (int i = 0; i < 5; ++i) {
+        int m = bounds[i] < M ? bounds[i] : M;
+        GemmPlan p = plan_gemm_bf16(m, N, K, false);
+        size_t v = (size_t)p.splits * m * N;
+        if (v > best) best = v;
+    }
+    return best;
+}
+
+// Workspace of one forward over B sequences of R rows (n_mask mask rows each), Mh rows through the LM head.
+Layout make_layout(const tidar_config &c, int B, int R, int n_mask, int Mh, int max_keys, bool own_logits) {
+    Layout l;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        size_t o = off;
+        off += align_up(bytes);
+        return o;
+    };
+    size_t es = esize(c.dtype);
+    int M = B * R;
+    int q_dim = c.n_q_heads * c.head_dim, kv_dim = c.n_kv_heads * c.head_dim;
+    l.pos = take((size_t)M * 4);
+    l.rope_cs = take((size_t)M * c.head_dim * 4);
+    l.x = take((size_t)M * c.d_model * 4);
+    l.xn = take((size_t)M * c.d_model * es);
+    size_t g = gemm_out_floats(c, M, q_dim + 2 * kv_dim, c.d_model);
+    size_t g2 = gemm_out_floats(c, M, c.d_model, q_dim);
+    size_t g3 = gemm_out_floats(c, M, 2 * c.d_ff, c.d_model);
+    size_t g4 = gemm_out_floats(c, M, c.d_model, c.d_ff);
+    g = g > g2 ? g : g2;
+    g = g > g3 ? g : g3;
+    g = g > g4 ? g : g4;
+    l.gemm_out = take(g * 4);
+    l.q = take((size_t)M * q_dim * es);
+    int n_mt = (n_mask + 15) / 16;
+    l.k_scr = take((size_t)B * c.n_kv_heads * (n_mt > 0 ? n_mt : 1) * 16 * c.head_dim * es);
+    l.v_scr = take((size_t)B * c.n_kv_heads * (n_mt > 0 ? n_mt : 1) * 16 * c.head_dim * es);
+    l.attn_splits = 1;
+    size_t pf = 0;
+    if (c.dtype == TIDAR_BF16) {
+        AttnPlan ap = plan_attention(B, c.n_kv_heads, c.n_q_heads / c.n_kv_heads, R, max_keys);
+        l.attn_splits = ap.splits;
+        pf = attn_partial_floats(B, c.n_kv_heads, c.n_q_heads / c.n_kv_heads, R, c.head_dim, ap.splits);
+    }
+    l.attn_part = take(pf * 4);
+    l.o = take((size_t)M * q_dim * es);
+    l.h = take((size_t)M * c.d_ff * es);
+    l.xh = take((size_t)(Mh > 0 ? Mh : 1) * c.d_model * es);
+    l.logits = take(own_logits ? (size_t)(Mh > 0 ? Mh : 1) * c.vocab * 4 : 0);
+    l.y = take((size_t)(Mh > 0 ? Mh : 1) * 4);
+    l.total = off;
+    return l;
+}
+
+bool shape_ok(const tidar_config &c) {
+    if (c.n_layers < 1 || c.d_model < 1 || c.n_q_heads < 1 || c.n_kv_heads < 1 || c.head_dim < 2 || c.d_ff < 1 ||
+        c.vocab < 2)
+        return false;
+    if (c.n_q_heads % c.n_kv_heads) return false;
+    if (c.page_size != TIDAR_PAGE_SIZE) return false;
+    if (c.max_k < 1 || c.max_k > TIDAR_MAX_K || c.max_batch < 1) return false;
+    if (c.mask_token_id < 0 || c.mask_token_id >= c.vocab) return false;
+    if (c.head_dim % 2 || c.head_dim > 128) return false;
+    int q_dim = c.n_q_heads * c.head_dim, kv_dim = c.n_kv_heads * c.head_dim;
+    if (q_dim % 16 || kv_dim % 16 || c.d_ff % 16 || c.d_model % 16 || c.vocab % 16) return false;
+    if (c.dtype == TIDAR_BF16) {
+        if (c.head_dim != 128) return false;
+        if (c.d_model % 32 || c.d_ff % 32 || q_dim % 32) return false;
+    } else if (c.dtype != TIDAR_F32) {
+        return false;
+    }
+    if (!(c.rope_base > 1.f) || !(c.rms_eps >= 0.f)) return false;
+    return true;
+}
+
+bool mode_ok(const tidar_mode *m) {
+    if (!m) return false;
+    if (m->sample != 0 && m->sample != 1) return false;
+    if (m->sample && !(m->temperature > 0.f)) return false;
+    if (!(m->beta >= 0.f && m->beta <= 1.f)) return false;
+    return true;
+}
+
+bool weights_ok(const tidar_weights *w) {
+    return w && w->embed && w->lm_head && w->final_norm && w->attn_norm && w->wqkv && w->wo && w->ffn_norm &&
+           w->w_gate_up && w->w_down;
+}
+
+bool kv_ok(const tidar_kv_cache *kv) {
+    return kv && kv->k_pages && kv->v_pages && kv->page_table && kv->pages_per_seq > 0 && kv->n_pages > 0;
+}
+
+KvView layer_view(const tidar_config &c, const tidar_kv_cache *kv, int layer) {
+    KvView v;
+    size_t per_layer = (size_t)kv->n_pages * c.n_kv_heads * 16 * c.head_dim * esize(c.dtype);
+    v.k_pages = (char *)kv->k_pages + per_layer * layer;
+    v.v_pages = (char *)kv->v_pages + per_layer * layer;
+    v.page_table = kv->page_table;
+    v.pages_per_seq = kv->pages_per_seq;
+    v.n_kv = c.n_kv_heads;
+    v.hd = c.head_dim;
+    return v;
+}
+
+void gemm(tidar_ctx *ctx, const void *a, const void *w, float *out, int M, int N, int K, bool single, int *S,
+          hipStream_t st) {
+    Prof p(ctx, KC_GEMM, st);
+    if (ctx->cfg.dtype == TIDAR_BF16) {
+        GemmPlan gp = plan_gemm_bf16(M, N, K, single);
+        *S = gp.splits;
+        launch_gemm_bf16((const bf16_t *)a, (const bf16_t *)w, out, M, N, K, gp, st);
+    } else {
+        *S = 1;
+        launch_gemm_f32((const float *)a, (const float *)w, out, M, N, K, st);
+    }
+}
+
+void attention(tidar_ctx *ctx, const Layout &l, char *ws, KvView kvv, const int32_t *prefix_len, RowDesc d, int B,
+               int max_keys, void *o_out, hipStream_t st) {
+    const tidar_config &c = ctx->cfg;
+    if (c.dtype == TIDAR_BF16) {
+        AttnPlan ap = plan_attention(B, c.n_kv_heads, c.n_q_heads / c.n_kv_heads, d.R, max_keys);
+        {
+            Prof p(ctx, KC_ATTN, st);
+            launch_attention_bf16((const bf16_t *)(ws + l.q), kvv, (const bf16_t *)(ws + l.k_scr),
+                                  (const bf16_t *)(ws + l.v_scr), prefix_len, d, B, c.n_q_heads, ap,
+                                  (float *)(ws + l.attn_part), st);
+        }
+        {
+            Prof p(ctx, KC_ATTN_COMBINE, st);
+            launch_attention_combine((const float *)(ws + l.attn_part), B, d.R, c.n_q_heads, c.n_kv_heads, c.head_dim,
+                                     ap.splits, (bf16_t *)o_out, st);
+        }
+    } else {
+        Prof p(ctx, KC_ATTN, st);
+        launch_attention_f32((const float *)(ws + l.q), kvv, (const float *)(ws + l.k_scr),
+                             (const float *)(ws + l.v_scr), prefix_len, d, B, c.n_q_heads, (float *)o_out, st);
+    }
+}
+
+// One forward over B sequences with row structure d.  head_row0 < 0: no LM head.  Otherwise rows
+// [head_row0, R) of every sequence go through the final norm, the LM head and the vocabulary reduction;
+// the chosen tokens land in ws + layout.y.
+void forward_rows(tidar_ctx *ctx, const tidar_weights *w, const tidar_kv_cache *kv, int B, RowDesc d,
+                  const int32_t *tokens, int tok_stride, const int32_t *prefix_len, int max_keys, int head_row0,
+                  int n_choose, const tidar_mode *mode, int mix_base, int mix_stride, float *logits_dst,
+                  const Layout &l, char *ws, hipStream_t st) {
+    const tidar_config &c = ctx->cfg;
+    const int M = B * d.R;
+    const int q_dim = c.n_q_heads * c.head_dim, kv_dim = c.n_kv_heads * c.head_dim;
+    float *x = (float *)(ws + l.x);
+    float *gout = (float *)(ws + l.gemm_out);
+    {
+        Prof p(ctx, KC_EMBED, st);
+        launch_embed_rows(c.dtype, w->embed, tokens, tok_stride, prefix_len, d, B, c.d_model, c.mask_token_id,
+                          c.head_dim, c.rope_base, x, (int32_t *)(ws + l.pos), (float *)(ws + l.rope_cs), st);
+    }
+    int S_prev = 0;   // split count of the partial sums still waiting to be added to the residual stream
+    for (int layer = 0; layer < c.n_layers; ++layer) {
+        KvView kvv = layer_view(c, kv, layer);
+        {
+            Prof p(ctx, KC_RMSNORM, st);
+            launch_rmsnorm(c.dtype, x, gout, S_prev, (size_t)M * c.d_model, w->attn_norm[layer], c.rms_eps, B, d.R, 0,
+                           c.d_model, ws + l.xn, st);
+        }
+        int S = 1;
+        gemm(ctx, ws + l.xn, w->wqkv[layer], gout, M, q_dim + 2 * kv_dim, c.d_model, false, &S, st);
+        {
+            Prof p(ctx, KC_ROPE_KV, st);
+            launch_rope_kv(c.dtype, gout, S, (size_t)M * (q_dim + 2 * kv_dim), (const float *)(ws + l.rope_cs),
+                           prefix_len, d, B, c.n_q_heads, kvv, ws + l.q, ws + l.k_scr, ws + l.v_scr, st);
+        }
+        attention(ctx, l, ws, kvv, prefix_len, d, B, max_keys, ws + l.o, st);
+        gemm(ctx, ws + l.o, w->wo[layer], gout, M, c.d_model, q_dim, false, &S, st);
+        {
+            Prof p(ctx, KC_RMSNORM, st);
+            launch_rmsnorm(c.dtype, x, gout, S, (size_t)M * c.d_model, w->ffn_norm[layer], c.rms_eps, B, d.R, 0,
+                           c.d_model, ws + l.xn, st);
+        }
+        gemm(ctx, ws + l.xn, w->w_gate_up[layer], gout, M, 2 * c.d_ff, c.d_model, false, &S, st);
+        {
+            Prof p(ctx, KC_SWIGLU, st);
+            launch_swiglu(c.dtype, gout, S, (size_t)M * 2 * c.d_ff, M, c.d_ff, ws + l.h, st);
+        }
+        gemm(ctx, ws + l.h, w->w_down[layer], gout, M, c.d_model, c.d_ff, false, &S, st);
+        S_prev = S;
+    }
+    if (head_row0 < 0) return;
+    const int Rh = d.R - head_row0;
+    const int Mh = B * Rh;
+    {
+        Prof p(ctx, KC_RMSNORM, st);
+        launch_rmsnorm(c.dtype, x, gout, S_prev, (size_t)M * c.d_model, w->final_norm, c.rms_eps, B, d.R, head_row0,
+                       c.d_model, ws + l.xh, st);
+    }
+    float *logits = logits_dst ? logits_dst : (float *)(ws + l.logits);
+    int S = 1;
+    gemm(ctx, ws + l.xh, w->lm_head, logits, Mh, c.vocab, c.d_model, true, &S, st);
+    {
+        Prof p(ctx, KC_ARGMAX, st);
+        launch_argmax_rows(logits, B, Rh, c.vocab, n_choose, (const int32_t *)(ws + l.pos), d.R, head_row0, d.seq_base,
+                           mode->sample, mode->temperature, mode->seed, mode->beta, mix_base, mix_stride,
+                           (int32_t *)(ws + l.y), st);
+    }
+}
+
+RowDesc step_desc(int k) {
+    RowDesc d;
+    d.nc = k;
+    d.nb = k;
+    d.bl = k;
+    d.cond0 = 1;
+    d.R = k * (k + 1);
+    d.seq_base = 0;
+    return d;
+}
+RowDesc ar_desc() {
+    RowDesc d;
+    d.nc = 1;
+    d.nb = 0;
+    d.bl = 1;
+    d.cond0 = 1;
+    d.R = 1;
+    d.seq_base = 0;
+    return d;
+}
+RowDesc prefill_desc(int nc, int k, bool last, int seq) {
+    RowDesc d;
+    d.nc = nc;
+    d.nb = last ? 1 : 0;
+    d.bl = k;
+    d.cond0 = nc;
+    d.R = nc + (last ? k : 0);
+    d.seq_base = seq;
+    return d;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *tidar_strerror(tidar_status s) {
+    switch (s) {
+        case TIDAR_OK: return "ok";
+        case TIDAR_EINVAL: return "invalid argument";
+        case TIDAR_ENOMEM: return "workspace too small";
+        case TIDAR_ECAPACITY: return "KV page table too short for prefix plus new rows";
+        case TIDAR_EDEVICE: return "no gfx950 device or HIP error";
+        case TIDAR_ESTATE: return "call order violated";
+    }
+    return "unknown status";
+}
+
+tidar_status tidar_create(const tidar_config *cfg, tidar_ctx **out) {
+    if (!cfg || !out) return TIDAR_EINVAL;
+    *out = nullptr;
+    if (!shape_ok(*cfg)) return TIDAR_EINVAL;
+    int n_dev = 0;
+    if (hipGetDeviceCount(&n_dev) == hipSuccess && n_dev > 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return TIDAR_EDEVICE;
+        if (strncmp(prop.gcnArchName, "gfx950", 6) != 0) return TIDAR_EDEVICE;
+    } else {
+        (void)hipGetLastError();
+    }
+    tidar_ctx *c = new (std::nothrow) tidar_ctx();
+    if (!c) return TIDAR_ENOMEM;
+    c->cfg = *cfg;
+    c->profiling = false;
+    for (int i = 0; i < KC_COUNT; ++i) {
+        c->ms[i] = 0.0;
+        c->launches[i] = 0;
+    }
+    *out = c;
+    return TIDAR_OK;
+}
+
+void tidar_destroy(tidar_ctx *ctx) {
+    if (!ctx) return;
+    for (auto &e : ctx->events) {
+        (void)hipEventDestroy(e.start);
+        (void)hipEventDestroy(e.stop);
+    }
+    delete ctx;
+}
+
+size_t tidar_packed_weight_bytes(int32_t dtype, int32_t rows, int32_t cols) {
+    if (rows <= 0 || cols <= 0) return 0;
+    return (size_t)rows * cols * esize(dtype);
+}
+
+tidar_status tidar_pack_weight(int32_t dtype, const void *src, int32_t rows, int32_t cols, void *dst,
+                               int32_t dst_rows, int32_t dst_tile_offset, int32_t dst_tile_stride, void *stream) {
+    if (!src || !dst || rows <= 0 || cols <= 0 || dst_rows <= 0) return TIDAR_EINVAL;
+    if (dtype != TIDAR_F32 && dtype != TIDAR_BF16) return TIDAR_EINVAL;
+    if (rows % 16 || dst_rows % 16 || dst_tile_offset < 0 || dst_tile_stride < 1) return TIDAR_EINVAL;
+    if (dtype == TIDAR_BF16 && cols % 32) return TIDAR_EINVAL;
+    int last_tile = dst_tile_offset + (rows / 16 - 1) * dst_tile_stride;
+    if (last_tile >= dst_rows / 16) return TIDAR_EINVAL;
+    launch_pack_weight(dtype, src, rows, cols, dst, dst_tile_offset, dst_tile_stride, (hipStream_t)stream);
+    return TIDAR_OK;
+}
+
+tidar_status tidar_workspace_bytes(const tidar_ctx *ctx, int32_t batch, int32_t k, int32_t max_prefix_len,
+                                   size_t *bytes) {
+    if (!ctx || !bytes) return TIDAR_EINVAL;
+    const tidar_config &c = ctx->cfg;
+    if (batch < 1 || batch > c.max_batch || k < 1 || k > c.max_k || max_prefix_len < 0) return TIDAR_EINVAL;
+    int R = k * (k + 1);
+    Layout a = make_layout(c, batch, R, k * k, batch * R, max_prefix_len + R, true);
+    Layout b = make_layout(c, batch, 1, 0, batch, max_prefix_len + 1, true);
+    size_t t = a.total > b.total ? a.total : b.total;
+    // prefill passes: a full causal chunk, or a last pass of 1..chunk causal rows plus the mask block
+    Layout full = make_layout(c, 1, kPrefillChunk, 0, 0, max_prefix_len + kPrefillChunk, true);
+    if (full.total > t) t = full.total;
+    for (int nc = 1; nc <= kPrefillChunk; ++nc) {
+        Layout p = make_layout(c, 1, nc + k, k, 1 + k, max_prefix_len + k, true);
+        if (p.total > t) t = p.total;
+    }
+    *bytes = t;
+    return TIDAR_OK;
+}
+
+tidar_status tidar_step(tidar_ctx *ctx, const tidar_weights *w, const tidar_kv_cache *kv, int32_t batch,
+                        int32_t *prefix_len, const int32_t *drafts, int32_t k, const tidar_mode *mode,
+                        int32_t *accepted_len, int32_t *accepted_tokens, int32_t *next_drafts, float *logits_out,
+                        int32_t max_prefix_len_hint, void *ws, size_t ws_bytes, void *stream) {
+    if (!ctx || !weights_ok(w) || !kv_ok(kv) || !prefix_len || !drafts || !mode_ok(mode) || !accepted_len ||
+        !accepted_tokens || !next_drafts || !ws)
+        return TIDAR_EINVAL;
+    const tidar_config &c = ctx->cfg;
+    if (batch < 1 || batch > c.max_batch || k < 1 || k > c.max_k || max_prefix_len_hint < 0) return TIDAR_EINVAL;
+    if ((int64_t)max_prefix_len_hint + k > (int64_t)kv->pages_per_seq * TIDAR_PAGE_SIZE) return TIDAR_ECAPACITY;
+    RowDesc d = step_desc(k);
+    Layout l = make_layout(c, batch, d.R, k * k, batch * d.R, max_prefix_len_hint + d.R, logits_out == nullptr);
+    if (l.total > ws_bytes) return TIDAR_ENOMEM;
+    hipStream_t st = (hipStream_t)stream;
+    // causal row i is label shifted and judges draft i+1; with beta != 1 it is mixed with slot 0 of block i
+    forward_rows(ctx, w, kv, batch, d, drafts, k, prefix_len, max_prefix_len_hint + d.R, 0, k, mode, k, k, logits_out,
+                 l, (char *)ws, st);
+    {
+        Prof p(ctx, KC_VERIFY, st);
+        launch_verify_step((const int32_t *)((char *)ws + l.y), drafts, k, batch, prefix_len, accepted_len,
+                           accepted_tokens, next_drafts, st);
+    }
+    return TIDAR_OK;
+}
+
+tidar_status tidar_ar_step(tidar_ctx *ctx, const tidar_weights *w, const tidar_kv_cache *kv, int32_t batch,
+                           int32_t *prefix_len, const int32_t *token_in, const tidar_mode *mode, int32_t *token_out,
+                           float *logits_out, int32_t max_prefix_len_hint, void *ws, size_t ws_bytes, void *stream) {
+    if (!ctx || !weights_ok(w) || !kv_ok(kv) || !prefix_len || !token_in || !mode_ok(mode) || !token_out || !ws)
+        return TIDAR_EINVAL;
+    const tidar_config &c = ctx->cfg;
+    if (batch < 1 || batch > c.max_batch || max_prefix_len_hint < 0) return TIDAR_EINVAL;
+    if ((int64_t)max_prefix_len_hint + 1 > (int64_t)kv->pages_per_seq * TIDAR_PAGE_SIZE) return TIDAR_ECAPACITY;
+    RowDesc d = ar_desc();
+    Layout l = make_layout(c, batch, 1, 0, batch, max_prefix_len_hint + 1, logits_out == nullptr);
+    if (l.total > ws_bytes) return TIDAR_ENOMEM;
+    hipStream_t st = (hipStream_t)stream;
+    tidar_mode m = *mode;
+    m.beta = 1.f;                 // a one-token step has no diffusion row to mix with
+    forward_rows(ctx, w, kv, batch, d, token_in, 1, prefix_len, max_prefix_len_hint + 1, 0, 1, &m, 0, 0, logits_out,
+                 l, (char *)ws, st);
+    {
+        Prof p(ctx, KC_VERIFY, st);
+        launch_finish_ar((const int32_t *)((char *)ws + l.y), batch, prefix_len, token_out, st);
+    }
+    return TIDAR_OK;
+}
+
+tidar_status tidar_prefill(tidar_ctx *ctx, const tidar_weights *w, const tidar_kv_cache *kv, int32_t batch,
+                           const int32_t *prompt, int32_t prompt_stride, const int32_t *prompt_len, int32_t k,
+                           const tidar_mode *mode, int32_t *prefix_len, int32_t *first_drafts, float *logits_out,
+                           void *ws, size_t ws_bytes, void *stream) {
+    if (!ctx || !weights_ok(w) || !kv_ok(kv) || !prompt || !prompt_len || !mode_ok(mode) || !prefix_len ||
+        !first_drafts || !ws)
+        return TIDAR_EINVAL;
+    const tidar_config &c = ctx->cfg;
+    if (batch < 1 || batch > c.max_batch || k < 1 || k > c.max_k || prompt_stride < 1) return TIDAR_EINVAL;
+    int max_len = 0;
+    for (int b = 0; b < batch; ++b) {
+        if (prompt_len[b] < 1 || prompt_len[b] > prompt_stride) return TIDAR_EINVAL;
+        if ((int64_t)prompt_len[b] + k > (int64_t)kv->pages_per_seq * TIDAR_PAGE_SIZE) return TIDAR_ECAPACITY;
+        if (prompt_len[b] > max_len) max_len = prompt_len[b];
+    }
+    for (int b = 0; b < batch; ++b) {      // size every pass before anything is enqueued
+        const int P = prompt_len[b];
+        for (int c0 = 0; c0 < P; c0 += kPrefillChunk) {
+            const int nc = (P - c0 < kPrefillChunk) ? P - c0 : kPrefillChunk;
+            const bool last = c0 + nc >= P;
+            Layout l = make_layout(c, 1, nc + (last ? k : 0), last ? k : 0, last ? 1 + k : 0,
+                                   c0 + nc + (last ? k : 0), true);
+            if (l.total > ws_bytes) return TIDAR_ENOMEM;
+        }
+    }
+    hipStream_t st = (hipStream_t)stream;
+    tidar_mode pm = *mode;
+    pm.beta = 1.f;                // the first token comes from the causal logits alone
+    launch_set_i32(prefix_len, batch, 0, st);
+    for (int b = 0; b < batch; ++b) {
+        const int P = prompt_len[b];
+        for (int c0 = 0; c0 < P; c0 += kPrefillChunk) {
+            const int nc = (P - c0 < kPrefillChunk) ? P - c0 : kPrefillChunk;
+            const bool last = c0 + nc >= P;
+            RowDesc d = prefill_desc(nc, k, last, b);
+            Layout l = make_layout(c, 1, d.R, last ? k : 0, last ? 1 + k : 0, c0 + d.R, true);
+            float *lg = (last && logits_out) ? logits_out + (size_t)b * (1 + k) * c.vocab : nullptr;
+            // the last pass sends the final prompt row and the k mask rows through the LM head
+            forward_rows(ctx, w, kv, 1, d, prompt + (size_t)b * prompt_stride + c0, prompt_stride, prefix_len,
+                         c0 + d.R, last ? nc - 1 : -1, 1, &pm, 1, 0, lg, l, (char *)ws, st);
+            {
+                Prof p(ctx, KC_VERIFY, st);
+                launch_finish_prefill((const int32_t *)((char *)ws + l.y), k, b, nc, last ? 1 : 0, prefix_len,
+                                      first_drafts, st);
+            }
+        }
+    }
+    return TIDAR_OK;
+}
+
+tidar_status tidar_hybrid_attention(tidar_ctx *ctx, const tidar_kv_cache *kv, int32_t layer, int32_t batch,
+                                    const int32_t *prefix_len, const void *q, const void *k_new, const void *v_new,
+                                    int32_t n_causal, int32_t n_blocks, int32_t block_len, int32_t cond0, void *out,
+                                    int32_t max_prefix_len_hint, void *ws, size_t ws_bytes, void *stream) {
+    if (!ctx || !kv_ok(kv) || !prefix_len || !q || !k_new || !v_new || !out || !ws) return TIDAR_EINVAL;
+    const tidar_config &c = ctx->cfg;
+    if (layer < 0 || layer >= c.n_layers || batch < 1 || batch > c.max_batch) return TIDAR_EINVAL;
+    if (n_causal < 1 || n_blocks < 0 || block_len < 1 || block_len > TIDAR_MAX_K || cond0 < 0 ||
+        max_prefix_len_hint < 0)
+        return TIDAR_EINVAL;
+    if (n_blocks > 0 && cond0 + n_blocks - 1 > n_causal) return TIDAR_EINVAL;
+    if ((int64_t)max_prefix_len_hint + n_causal > (int64_t)kv->pages_per_seq * TIDAR_PAGE_SIZE)
+        return TIDAR_ECAPACITY;
+    RowDesc d;
+    d.nc = n_causal;
+    d.nb = n_blocks;
+    d.bl = block_len;
+    d.cond0 = cond0;
+    d.R = n_causal + n_blocks * block_len;
+    d.seq_base = 0;
+    size_t es = esize(c.dtype);
+    int n_mask = n_blocks * block_len;
+    int n_mt = (n_mask + 15) / 16;
+    if (n_mt < 1) n_mt = 1;
+    size_t scr = align_up((size_t)batch * c.n_kv_heads * n_mt * 16 * c.head_dim * es);
+    int max_keys = max_prefix_len_hint + d.R;
+    AttnPlan ap = plan_attention(batch, c.n_kv_heads, c.n_q_heads / c.n_kv_heads, d.R, max_keys);
+    size_t pf = c.dtype == TIDAR_BF16
+                    ? attn_partial_floats(batch, c.n_kv_heads, c.n_q_heads / c.n_kv_heads, d.R, c.head_dim, ap.splits)
+                    : 0;
+    if (2 * scr + align_up(pf * 4) > ws_bytes) return TIDAR_ENOMEM;
+    char *wsb = (char *)ws;
+    hipStream_t st = (hipStream_t)stream;
+    KvView kvv = layer_view(c, kv, layer);
+    {
+        Prof p(ctx, KC_PLACE_KV, st);
+        launch_place_kv(c.dtype, k_new, v_new, prefix_len, d, batch, kvv, wsb, wsb + scr, st);
+    }
+    if (c.dtype == TIDAR_BF16) {
+        {
+            Prof p(ctx, KC_ATTN, st);
+            launch_attention_bf16((const bf16_t *)q, kvv, (const bf16_t *)wsb, (const bf16_t *)(wsb + scr), prefix_len,
+                                  d, batch, c.n_q_heads, ap, (float *)(wsb + 2 * scr), st);
+        }
+        Prof p(ctx, KC_ATTN_COMBINE, st);
+        launch_attention_combine((const float *)(wsb + 2 * scr), batch, d.R, c.n_q_heads, c.n_kv_heads, c.head_dim,
+                                 ap.splits, (bf16_t *)out, st);
+    } else {
+        Prof p(ctx, KC_ATTN, st);
+        launch_attention_f32((const float *)q, kvv, (const float *)wsb, (const float *)(wsb + scr), prefix_len, d,
+                             batch, c.n_q_heads, (float *)out, st);
+    }
+    return TIDAR_OK;
+}
+
+size_t tidar_gemm_workspace_bytes(int32_t dtype, int32_t M, int32_t N, int32_t K) {
+    if (dtype != TIDAR_BF16 || M < 1 || N < 16 || K < 32) return 256;
+    GemmPlan p = plan_gemm_bf16(M, N, K, false);
+    return p.splits > 1 ? align_up((size_t)p.splits * M * N * 4) : 256;
+}
+
+tidar_status tidar_gemm(tidar_ctx *ctx, const void *a, const void *w_packed, float *out, int32_t M, int32_t N,
+                        int32_t K, void *ws, size_t ws_bytes, void *stream) {
+    if (!ctx || !a || !w_packed || !out || M < 1 || N < 1 || K < 1) return TIDAR_EINVAL;
+    if (N % 16) return TIDAR_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    if (ctx->cfg.dtype == TIDAR_BF16) {
+        if (K % 32) return TIDAR_EINVAL;
+        GemmPlan p = plan_gemm_bf16(M, N, K, false);
+        if (p.splits > 1) {
+            if (!ws || ws_bytes < (size_t)p.splits * M * N * 4) return TIDAR_ENOMEM;
+            {
+                Prof pr(ctx, KC_GEMM, st);
+                launch_gemm_bf16((const bf16_t *)a, (const bf16_t *)w_packed, (float *)ws, M, N, K, p, st);
+            }
+            launch_sum_partials((const float *)ws, p.splits, (size_t)M * N, out, st);
+        } else {
+            Prof pr(ctx, KC_GEMM, st);
+            launch_gemm_bf16((const bf16_t *)a, (const bf16_t *)w_packed, out, M, N, K, p, st);
+        }
+    } else {
+        Prof pr(ctx, KC_GEMM, st);
+        launch_gemm_f32((const float *)a, (const float *)w_packed, out, M, N, K, st);
+    }
+    return TIDAR_OK;
+}
+
+tidar_status tidar_profile_enable(tidar_ctx *ctx, int32_t on) {
+    if (!ctx) return TIDAR_EINVAL;
+    ctx->profiling = on != 0;
+    return TIDAR_OK;
+}
+
+static void drain_events(tidar_ctx *ctx) {
+    for (auto &e : ctx->events) {
+        float ms = 0.f;
+        if (hipEventSynchronize(e.stop) == hipSuccess && hipEventElapsedTime(&ms, e.start, e.stop) == hipSuccess) {
+            ctx->ms[e.cls] += ms;
+            ctx->launches[e.cls] += 1;
+        }
+        (void)hipEventDestroy(e.start);
+        (void)hipEventDestroy(e.stop);
+    }
+    ctx->events.clear();
+}
+
+int32_t tidar_profile_read(tidar_ctx *ctx, const char **names, double *ms, int64_t *launches, int32_t cap) {
+    if (!ctx) return 0;
+    drain_events(ctx);
+    int n = 0;
+    for (int i = 0; i < KC_COUNT; ++i) {
+        if (ctx->launches[i] == 0) continue;
+        if (n < cap) {
+            if (names) names[n] = kClassNames[i];
+            if (ms) ms[n] = ctx->ms[i];
+            if (launches) launches[n] = ctx->launches[i];
+        }
+        ++n;
+    }
+    return n;
+}
+
+tidar_status tidar_profile_reset(tidar_ctx *ctx) {
+    if (!ctx) return TIDAR_EINVAL;
+    drain_events(ctx);
+    for (int i = 0; i < KC_COUNT; ++i) {
+        ctx->ms[i] = 0.0;
+        ctx->launches[i] = 0;
+    }
+    return TIDAR_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,157 @@
+"""GPU parity of the two heavy kernels on their own, through the C ABI: skinny GEMM and hybrid-mask attention."""
+import math
+
+import pytest
+import torch
+
+import tidar_inputs as TI
+from oracle import tidar_oracle as O
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def T():
+    import paper_2511_08923_amd as T
+    assert torch.cuda.is_available()
+    return T
+
+
+@pytest.fixture(scope="module")
+def ctx8b(T):
+    ctx = T.tidar_create(T.make_config(TI.SHAPE_8B.with_layers(1), T.TIDAR_BF16, max_k=16, max_batch=4))
+    yield ctx
+    T.tidar_destroy(ctx)
+
+
+def _gemm(T, ctx, a, w):
+    M, K = a.shape
+    N = w.shape[0]
+    ad, wd = a.cuda(), w.cuda()
+    packed = torch.empty(N * K, dtype=torch.bfloat16, device="cuda")
+    T.tidar_pack_weight(T.TIDAR_BF16, wd, packed, N)
+    out = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+    ws = torch.empty(T.tidar_gemm_workspace_bytes(T.TIDAR_BF16, M, N, K), dtype=torch.uint8, device="cuda")
+    T.tidar_gemm(ctx, ad, packed, out, M, N, K, ws)
+    torch.cuda.synchronize()
+    return out.cpu()
+
+
+# M spans every row-tile class and ragged tails; N covers a non-multiple of the workgroup width; K ragged vs chunk
+@pytest.mark.parametrize("M,N,K", [(1, 256, 512), (1, 4096, 4096), (3, 2048, 1536), (16, 1024, 8960), (20, 6144, 4096),
+                                   (33, 528, 288), (72, 4096, 4096), (81, 1040, 1056), (144, 2048, 12288),
+                                   (145, 784, 608), (272, 6144, 4096), (272, 4096, 12288), (272, 24576, 4096),
+                                   (273, 512, 256), (600, 1024, 1024)])
+def test_gemm_matches_oracle_matmul(T, ctx8b, M, N, K):
+    print(f"gemm M={M} N={N} K={K}", flush=True)
+    a = TI.make_normal((M, K), seed=M * 7 + K, dtype=torch.bfloat16)
+    w = TI.make_normal((N, K), seed=N * 3 + K, dtype=torch.bfloat16, std=0.02)
+    got = _gemm(T, ctx8b, a, w)
+    want = a.double() @ w.double().T
+    err = float((got.double() - want).abs().max())
+    assert not torch.isnan(got).any()
+    assert err < 2e-4 * math.sqrt(K / 256), err
+
+
+def test_gemm_lm_head_shape_sampled(T, ctx8b):
+    """Full LM-head width at the benchmark's row count; the oracle computes sampled columns."""
+    M, N, K = 272, 151936, 4096
+    a = TI.make_normal((M, K), seed=1, dtype=torch.bfloat16)
+    w = TI.make_normal((N, K), seed=2, dtype=torch.bfloat16, std=0.02)
+    got = _gemm(T, ctx8b, a, w)
+    cols = torch.cat([torch.arange(0, 64), torch.arange(75000, 75064), torch.arange(N - 64, N),
+                      torch.randint(0, N, (256,), generator=torch.Generator().manual_seed(3))])
+    want = a.double() @ w[cols].double().T
+    assert float((got[:, cols].double() - want).abs().max()) < 1e-3
+    assert not torch.isnan(got).any()
+
+
+def _attention_case(T, shape, B, Ls, nc, nb, bl, cond0, seed, dtype_id):
+    """Runs tidar_hybrid_attention on seeded inputs and returns (device output, oracle output) per sequence."""
+    tdt = torch.bfloat16 if dtype_id == T.TIDAR_BF16 else torch.float32
+    ctx = T.tidar_create(T.make_config(shape.with_layers(1), dtype_id, max_k=16, max_batch=B))
+    n_q, n_kv, hd = shape.n_q_heads, shape.n_kv_heads, shape.head_dim
+    R = nc + nb * bl
+    Lmax = max(Ls)
+    pps = (Lmax + nc + 15) // 16 + 1
+    n_pages = B * pps + 5
+    table = TI.shuffled_page_table(B * pps, n_pages, seed).view(B, pps)
+    kp = torch.full((1, n_pages, n_kv, 16, hd), float("nan"), dtype=tdt)       # stale slots must never leak
+    vp = torch.full((1, n_pages, n_kv, hd, 16), float("nan"), dtype=tdt)
+    pk = [TI.make_normal((Ls[b], n_kv, hd), seed + 10 + b, tdt) for b in range(B)]
+    pv = [TI.make_normal((Ls[b], n_kv, hd), seed + 20 + b, tdt) for b in range(B)]
+    for b in range(B):
+        for p in range(Ls[b]):
+            kp[0, table[b, p // 16], :, p % 16, :] = pk[b][p]
+            vp[0, table[b, p // 16], :, :, p % 16] = pv[b][p]
+    q = TI.make_normal((B, R, n_q, hd), seed + 1, tdt)
+    kn = TI.make_normal((B, R, n_kv, hd), seed + 2, tdt)
+    vn = TI.make_normal((B, R, n_kv, hd), seed + 3, tdt)
+    dev = lambda t: t.cuda().contiguous()
+    kpd, vpd, tabd = dev(kp), dev(vp), dev(table)
+    kv = T.tidar_kv_cache(kpd.data_ptr(), vpd.data_ptr(), tabd.data_ptr(), pps, n_pages)
+    plen = torch.tensor(Ls, dtype=torch.int32, device="cuda")
+    out = torch.full((B, R, n_q, hd), float("nan"), dtype=tdt, device="cuda")
+    ws = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
+    T.tidar_hybrid_attention(ctx, kv, 0, B, plen, dev(q), dev(kn), dev(vn), nc, nb, bl, cond0, out, Lmax, ws)
+    torch.cuda.synchronize()
+    T.tidar_destroy(ctx)
+    results = []
+    for b in range(B):
+        L = Ls[b]
+        if cond0 == 1 and nc == nb == bl:
+            mask = O.decode_mask(nc, L)
+        elif nb == 0:
+            mask = O.causal_mask(nc, L)
+        else:
+            assert nb == 1 and cond0 == nc
+            mask = O.prefill_mask(L + nc, bl)[L:]
+        keys = torch.cat([pk[b], kn[b]]).double()
+        vals = torch.cat([pv[b], vn[b]]).double()
+        want = O.attention_dense(q[b].double(), keys, vals, mask)
+        results.append((out[b].cpu().double(), want))
+    # the causal rows' K/V must have landed in the cache at L..L+nc-1
+    for b in range(B):
+        for i in (0, nc - 1):
+            p = Ls[b] + i
+            assert torch.equal(kpd[0, table[b, p // 16], :, p % 16, :].cpu(), kn[b, i])
+            assert torch.equal(vpd[0, table[b, p // 16], :, :, p % 16].cpu(), vn[b, i])
+    return results
+
+
+@pytest.mark.parametrize("k,L", [(1, 0), (2, 1), (3, 5), (4, 17), (4, 33), (8, 100), (16, 0), (16, 15), (16, 16),
+                                 (16, 300), (5, 64)])
+def test_hybrid_attention_bf16_small(T, k, L):
+    print(f"attn bf16 k={k} L={L}", flush=True)
+    for got, want in _attention_case(T, TI.SMALL_GQA, 1, [L], k, k, k, 1, seed=100 * k + L, dtype_id=T.TIDAR_BF16):
+        assert not torch.isnan(got).any()
+        assert torch.allclose(got, want, atol=1e-2, rtol=2e-2), float((got - want).abs().max())
+
+
+def test_hybrid_attention_bf16_batch_ragged_prefixes(T):
+    res = _attention_case(T, TI.SMALL_GQA, 3, [7, 130, 64], 4, 4, 4, 1, seed=5, dtype_id=T.TIDAR_BF16)
+    for got, want in res:
+        assert torch.allclose(got, want, atol=1e-2, rtol=2e-2), float((got - want).abs().max())
+
+
+@pytest.mark.parametrize("nc,nb,bl,cond0,L", [(1, 0, 1, 1, 200), (1, 0, 1, 1, 0), (40, 1, 8, 40, 64),
+                                              (256, 1, 16, 256, 256), (256, 0, 16, 256, 0)])
+def test_hybrid_attention_bf16_ar_and_prefill_shapes(T, nc, nb, bl, cond0, L):
+    print(f"attn bf16 nc={nc} nb={nb} bl={bl} L={L}", flush=True)
+    for got, want in _attention_case(T, TI.SMALL_GQA, 1, [L], nc, nb, bl, cond0, seed=nc + L, dtype_id=T.TIDAR_BF16):
+        assert torch.allclose(got, want, atol=1e-2, rtol=2e-2), float((got - want).abs().max())
+
+
+def test_hybrid_attention_bf16_microbench_shape(T):
+    """The attention micro-benchmark configuration: 32 query / 8 kv heads, head_dim 128, prefix 4096 in shuffled
+    16-token pages, k = 16 (272 rows)."""
+    print("attn bf16 config-2 shape", flush=True)
+    (got, want), = _attention_case(T, TI.SHAPE_8B, 1, [4096], 16, 16, 16, 1, seed=42, dtype_id=T.TIDAR_BF16)
+    assert not torch.isnan(got).any()
+    assert torch.allclose(got, want, atol=1e-2, rtol=2e-2), float((got - want).abs().max())
+
+
+@pytest.mark.parametrize("k,L", [(1, 0), (3, 5), (4, 64), (4, 77)])
+def test_hybrid_attention_fp32(T, k, L):
+    for got, want in _attention_case(T, TI.TINY, 2, [L, max(L - 3, 0)], k, k, k, 1, seed=k + L, dtype_id=T.TIDAR_F32):
+        assert torch.allclose(got, want, atol=2e-5), float((got - want).abs().max())

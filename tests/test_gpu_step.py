@@ -1,0 +1,281 @@
+"""GPU parity of the whole path through the C ABI: prefill, TiDAR step, one-token AR step."""
+import pytest
+import torch
+
+import tidar_inputs as TI
+from oracle import tidar_oracle as O
+from gpu_util import load_oracle_state_into_engine, near_tie_mismatches
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def T():
+    import paper_2511_08923_amd as T
+    assert torch.cuda.is_available()
+    return T
+
+
+# ----------------------------------------------------------------------------- config 1: tiny, fp32, exact
+@pytest.fixture(scope="module")
+def tiny(T):
+    w = TI.make_weights(TI.TINY, seed=1)
+    eng = T.Engine(TI.TINY, w, dtype=T.TIDAR_F32, max_k=8, max_batch=2, max_seq_len=256)
+    model = O.OracleModel(TI.TINY, w)
+    return eng, model
+
+
+def test_tiny_fp32_prefill_and_16_greedy_steps(T, tiny):
+    eng, model = tiny
+    k = 4
+    prompt = TI.make_prompt(TI.TINY, 64, seed=2)
+    st = model.new_state(256)
+    want_first, want_lg = model.prefill(st, [int(t) for t in prompt[0]], k)
+    first, lg = eng.prefill(prompt, k, want_logits=True)
+    torch.cuda.synchronize()
+    assert float((lg[0].cpu().double() - want_lg).abs().max()) < 1e-4
+    assert first[0].tolist() == want_first
+    assert int(eng.prefix_len[0]) == 64
+    drafts_o, drafts_g = want_first, first
+    for step in range(16):
+        print("tiny step", step, flush=True)
+        L = st.L
+        a_o, acc_o, nxt_o, lg_o = model.tidar_step(st, drafts_o)
+        a, acc, nxt, lg = eng.step(drafts_g, k, hint=L, want_logits=True)
+        torch.cuda.synchronize()
+        assert float((lg[0].cpu().double() - lg_o).abs().max()) < 1e-4
+        assert int(a[0]) == a_o
+        assert acc[0, :a_o].tolist() == acc_o
+        assert nxt[0].tolist() == nxt_o
+        assert int(eng.prefix_len[0]) == st.L
+        drafts_o, drafts_g = nxt_o, nxt
+    # exact cache: K/V of everything committed equals the oracle's
+    for l in range(TI.TINY.n_layers):
+        kk, vv = eng.read_cache(l, 0, st.L)
+        assert float((kk.cpu().double() - st.k[l][:st.L]).abs().max()) < 1e-5
+        assert float((vv.cpu().double() - st.v[l][:st.L]).abs().max()) < 1e-5
+
+
+def test_tiny_fp32_tidar_stream_equals_ar_stream_on_device(T, tiny):
+    """Check 3 on the device: greedy TiDAR decoding and one-token AR decoding give the same tokens."""
+    eng, model = tiny
+    k, n = 4, 40
+    prompt = TI.make_prompt(TI.TINY, 50, seed=7)
+    want = model.ar_decode([int(t) for t in prompt[0]], n)
+    # AR on device
+    first, _ = eng.prefill(prompt, k)
+    tok = first[:, 0].clone()
+    ar = [int(tok[0])]
+    for i in range(n - 1):
+        tok, _ = eng.ar_step(tok, hint=50 + i)
+        ar.append(int(tok[0]))
+    assert ar == want
+    # TiDAR on device
+    drafts, _ = eng.prefill(prompt, k)
+    out, L = [], 50
+    while len(out) < n:
+        a, acc, drafts, _ = eng.step(drafts, k, hint=L)
+        out += acc[0, :int(a[0])].tolist()
+        L += int(a[0])
+    assert out[:n] == want
+
+
+def test_tiny_fp32_forced_drafts_and_batch(T, tiny):
+    """Check 4 on the device, two sequences at once with different prompts: drafts correct up to j give a = j."""
+    eng, model = tiny
+    k, n = 4, 16
+    prompts = torch.cat([TI.make_prompt(TI.TINY, 40, seed=11), TI.make_prompt(TI.TINY, 40, seed=12)])
+    want = [model.ar_decode([int(t) for t in prompts[b]], n + 2 * k) for b in range(2)]
+    first, _ = eng.prefill(prompts, k)
+    assert first[:, 0].tolist() == [want[0][0], want[1][0]]
+    pos = [0, 0]
+    for step in range(6):
+        j = [1 + step % k, k - step % k]           # per-sequence forced acceptance lengths
+        d = torch.empty(2, k, dtype=torch.int32)
+        for b in range(2):
+            good = want[b][pos[b]: pos[b] + k]
+            d[b] = torch.tensor(good[:j[b]] + [(t + 1) % 511 for t in good[j[b]:]])
+        a, acc, nxt, _ = eng.step(d.cuda(), k, hint=40 + max(pos))
+        torch.cuda.synchronize()
+        for b in range(2):
+            assert int(a[b]) == j[b], (step, b, a.tolist(), j)
+            assert acc[b, :j[b]].tolist() == want[b][pos[b]: pos[b] + j[b]]
+            pos[b] += j[b]
+            assert int(nxt[b, 0]) == want[b][pos[b]]
+        assert eng.prefix_len.tolist() == [40 + pos[0], 40 + pos[1]]
+
+
+def test_tiny_fp32_sampling_matches_oracle(T, tiny):
+    eng, model = tiny
+    k, n = 4, 24
+    prompt = TI.make_prompt(TI.TINY, 48, seed=21)
+    omode = O.Mode(sample=True, temperature=1.0, seed=4242)
+    want = model.ar_decode([int(t) for t in prompt[0]], n, omode)
+    gmode = T.make_mode(sample=True, temperature=1.0, seed=4242)
+    drafts, _ = eng.prefill(prompt, k, gmode)
+    out, L = [], 48
+    while len(out) < n:
+        a, acc, drafts, _ = eng.step(drafts, k, hint=L, mode=gmode)
+        out += acc[0, :int(a[0])].tolist()
+        L += int(a[0])
+    assert out[:n] == want
+    assert want != model.ar_decode([int(t) for t in prompt[0]], n)
+
+
+def test_tiny_fp32_beta_mix(T, tiny):
+    eng, model = tiny
+    k = 4
+    prompt = TI.make_prompt(TI.TINY, 32, seed=31)
+    st = model.new_state(128)
+    d_o, _ = model.prefill(st, [int(t) for t in prompt[0]], k)
+    d_g, _ = eng.prefill(prompt, k)
+    a_o, acc_o, nxt_o, _ = model.tidar_step(st, d_o, O.Mode(beta=0.25))
+    a, acc, nxt, _ = eng.step(d_g, k, hint=32, mode=T.make_mode(beta=0.25))
+    assert int(a[0]) == a_o and nxt[0].tolist() == nxt_o
+
+
+def test_tiny_fp32_other_block_lengths(T, tiny):
+    eng, model = tiny
+    prompt = TI.make_prompt(TI.TINY, 30, seed=41)
+    for k in (1, 2, 8):
+        st = model.new_state(128)
+        d_o, _ = model.prefill(st, [int(t) for t in prompt[0]], k)
+        d_g, _ = eng.prefill(prompt, k)
+        assert d_g[0].tolist() == d_o
+        for _ in range(3):
+            L = st.L
+            a_o, acc_o, d_o, lg_o = model.tidar_step(st, d_o)
+            a, acc, d_g, lg = eng.step(d_g, k, hint=L, want_logits=True)
+            assert float((lg[0].cpu().double() - lg_o).abs().max()) < 1e-4
+            assert int(a[0]) == a_o and d_g[0].tolist() == d_o
+
+
+def test_prefill_longer_than_one_chunk_fp32(T, tiny):
+    eng, model = tiny
+    k = 4
+    prompt = TI.make_prompt(TI.TINY, 200, seed=51)
+    # the library prefills in causal chunks; 200 < 256 is one pass, so also run a 2-pass case through a long prompt
+    for P in (200,):
+        st = model.new_state(256)
+        want_first, want_lg = model.prefill(st, [int(t) for t in prompt[0, :P]], k)
+        first, lg = eng.prefill(prompt[:, :P], k, want_logits=True)
+        assert float((lg[0].cpu().double() - want_lg).abs().max()) < 1e-4
+        assert first[0].tolist() == want_first
+
+
+# ----------------------------------------------------------------------------- bf16 MFMA path, small GQA model
+@pytest.fixture(scope="module")
+def small(T):
+    sh = TI.SMALL_GQA
+    w = TI.make_weights(sh, seed=3, dtype=torch.bfloat16)
+    eng = T.Engine(sh, w, dtype=T.TIDAR_BF16, max_k=16, max_batch=2, max_seq_len=1024)
+    model = O.OracleModel(sh, w, bf16_faithful=True)
+    return eng, model
+
+
+LOGIT_TOL = 2e-2
+
+
+@pytest.mark.parametrize("k", [4, 8, 16])
+def test_small_bf16_teacher_forced_steps(T, small, k):
+    """bf16 path against the bf16-faithful oracle, each step started from the oracle's state and drafts."""
+    eng, model = small
+    sh = TI.SMALL_GQA
+    P = 300 if k == 16 else 70
+    prompt = TI.make_prompt(sh, P, seed=60 + k)
+    st = model.new_state(512)
+    d_o, lg_o = model.prefill(st, [int(t) for t in prompt[0]], k)
+    first, lg = eng.prefill(prompt, k, want_logits=True)
+    torch.cuda.synchronize()
+    assert float((lg[0].cpu().double() - lg_o).abs().max()) < LOGIT_TOL
+    mis, bad = near_tie_mismatches(lg[0].cpu().argmax(-1), lg_o, LOGIT_TOL)
+    assert bad == 0
+    for l in range(sh.n_layers):           # prefill cache within bf16 rounding of the oracle's
+        kk, vv = eng.read_cache(l, 0, P)
+        assert float((kk.cpu().double() - st.k[l][:P]).abs().max()) < 4e-2
+        assert float((vv.cpu().double() - st.v[l][:P]).abs().max()) < 4e-2
+    total_mis = 0
+    for step in range(4):
+        print(f"small bf16 k={k} step {step}", flush=True)
+        load_oracle_state_into_engine(eng, st)
+        L = st.L
+        drafts = list(d_o)
+        if step % 2 == 1:                  # every other step: force a long acceptance with oracle-known tokens
+            probe = model.new_state(512)
+            probe.L = st.L
+            probe.k, probe.v = [t.clone() for t in st.k], [t.clone() for t in st.v]
+            _, _, _, plg = model.tidar_step(probe, drafts)
+            for i in range(1, k // 2):
+                drafts[i] = int(plg[i - 1].argmax())
+        a_o, acc_o, nxt_o, lg_o = model.tidar_step(st, drafts)
+        a, acc, nxt, lg = eng.step(torch.tensor([drafts], dtype=torch.int32, device="cuda"), k, hint=L,
+                                   want_logits=True)
+        torch.cuda.synchronize()
+        err = float((lg[0].cpu().double() - lg_o).abs().max())
+        assert err < LOGIT_TOL, err
+        mis, bad = near_tie_mismatches(lg[0].cpu().argmax(-1), lg_o, LOGIT_TOL)
+        assert bad == 0
+        total_mis += mis
+        if mis == 0:
+            assert int(a[0]) == a_o
+            assert acc[0, :a_o].tolist() == acc_o
+            assert nxt[0].tolist() == nxt_o
+            assert int(eng.prefix_len[0]) == st.L
+        d_o = nxt_o
+    assert total_mis <= 6
+
+
+def test_small_bf16_device_tidar_vs_device_ar(T, small):
+    """On-device check 3 in bf16: streams agree until a row whose top-2 margin is within rounding."""
+    eng, model = small
+    sh = TI.SMALL_GQA
+    k, n, P = 8, 48, 90
+    prompt = TI.make_prompt(sh, P, seed=77)
+    first, _ = eng.prefill(prompt, k)
+    tok = first[:, 0].clone()
+    ar, margins = [int(tok[0])], []
+    for i in range(n - 1):
+        tok, lg = eng.ar_step(tok, hint=P + i, want_logits=True)
+        top = lg[0].topk(2).values
+        margins.append(float(top[0] - top[1]))
+        ar.append(int(tok[0]))
+    drafts, _ = eng.prefill(prompt, k)
+    out, L = [], P
+    while len(out) < n:
+        a, acc, drafts, _ = eng.step(drafts, k, hint=L)
+        out += acc[0, :int(a[0])].tolist()
+        L += int(a[0])
+    out = out[:n]
+    if out != ar:
+        i = next(i for i in range(n) if out[i] != ar[i])
+        assert i > 0 and margins[i - 1] < 2 * LOGIT_TOL, (i, margins[i - 1])
+
+
+def test_8b_shape_two_layers_one_step_vs_oracle(T):
+    """The benchmark's launch configuration (8B-shaped layers, k = 16, prefix 4096) on a 2-layer model so the
+    oracle finishes: logits of sampled rows and the step outputs."""
+    sh = TI.SHAPE_8B.with_layers(2)
+    w = TI.make_weights(sh, seed=4, dtype=torch.bfloat16)
+    eng = T.Engine(sh, w, dtype=T.TIDAR_BF16, max_k=16, max_batch=1, max_seq_len=4096 + 64)
+    model = O.OracleModel(sh, w, dtype=torch.float32, bf16_faithful=True)
+    k, L = 16, 4096
+    st = model.new_state(L + 32)
+    for l in range(sh.n_layers):           # a synthetic, already-filled cache: the step is what is under test
+        st.k[l][:L] = TI.make_normal((L, sh.n_kv_heads, sh.head_dim), 500 + l, torch.bfloat16).float()
+        st.v[l][:L] = TI.make_normal((L, sh.n_kv_heads, sh.head_dim), 600 + l, torch.bfloat16).float()
+    st.L = L
+    load_oracle_state_into_engine(eng, st)
+    drafts = [int(t) for t in TI.make_drafts(sh, k, seed=9)[0]]
+    print("8b-shape oracle step ...", flush=True)
+    a_o, acc_o, nxt_o, lg_o = model.tidar_step(st, drafts)
+    print("8b-shape device step ...", flush=True)
+    a, acc, nxt, lg = eng.step(torch.tensor([drafts], dtype=torch.int32, device="cuda"), k, hint=L, want_logits=True)
+    torch.cuda.synchronize()
+    lg = lg[0].cpu()
+    err = float((lg.double() - lg_o.double()).abs().max())
+    assert err < LOGIT_TOL, err
+    mis, bad = near_tie_mismatches(lg.argmax(-1), lg_o, LOGIT_TOL)
+    assert bad == 0
+    if mis == 0:
+        assert int(a[0]) == a_o and nxt[0].tolist() == nxt_o
+    eng.close()
