@@ -35,9 +35,13 @@ Readings taken where the paper is silent (figures are not available):
   F. argmax ties go to the lowest token id.
   J. RMSNorm eps 1e-6, RoPE pairs dimension i with i + head_dim/2, no biases.
   K. bf16-faithful mode rounds to bf16 at: normalised activations entering a
-     GEMM, Q and K after RoPE, V, softmax probabilities, attention output, the
+     GEMM, Q and K after RoPE, V, softmax numerators, attention output, the
      SwiGLU product; weights are bf16 values; the residual stream and all
-     accumulation stay wide.
+     accumulation stay wide.  The softmax numerator is rounded as
+     2^(s*log2(e) - ceil(max_row s*log2(e))): measured against a power-of-two
+     reference the rounded mantissa does not depend on which reference an
+     implementation happens to use, so any tiling order rounds the same way;
+     the denominator sums the rounded numerators.
 
 Parity status: every function below is pinned by tests/test_oracle_*.py
 (worked-example mask, closed-form counts, brute-force loops, an independent
@@ -176,11 +180,12 @@ def attention_dense(q: torch.Tensor, keys: torch.Tensor, vals: torch.Tensor, mas
         g = h // group
         s = (q[:, h, :] @ keys[:, g, :].T) * scale                             # [R, T]
         s = torch.where(mask, s, neg_inf)
-        s = s - s.max(dim=-1, keepdim=True).values
-        e = torch.exp(s)
+        if round_p:                                                             # reading K
+            s2 = s * math.log2(math.e)
+            e = round_bf16(torch.exp2(s2 - torch.ceil(s2.max(dim=-1, keepdim=True).values)))
+        else:
+            e = torch.exp(s - s.max(dim=-1, keepdim=True).values)
         p = e / e.sum(dim=-1, keepdim=True)
-        if round_p:
-            p = round_bf16(p)
         out[:, h, :] = p @ vals[:, g, :]
     return out
 

@@ -5,6 +5,9 @@
 // is staged once in LDS serves every query head that shares it.  Four waves split the query tiles; each wave
 // keeps its Q fragments, its O^T accumulators and its softmax state in registers for the whole key range.
 //
+// Softmax numerators are taken against an integral power-of-two reference (ceil of the running maximum in
+// log2 units): their bf16 rounding is then independent of the reference in force, i.e. of tiling and splits.
+//
 // Orientation: scores are formed transposed, S^T[key][q] = K . Q^T, so that in the MFMA result layout a lane
 // holds one query column and four keys per 16-key tile.  Exponentials of two such tiles are, without any data
 // movement, the B operand (P^T) of O^T[d][q] += V^T[d][key] . P^T[key][q].  V is kept transposed in HBM
@@ -246,7 +249,10 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
                 }
             mx = fmaxf(mx, __shfl_xor(mx, 16));
             mx = fmaxf(mx, __shfl_xor(mx, 32));
-            const float m_new = fmaxf(m_run[i], mx);
+            // the reference exponent is kept integral: numerators 2^(s - ref) then round to bf16 the same way
+            // whichever reference is current, so the result does not depend on tile order or split count,
+            // and every rescale below is by an exact power of two
+            const float m_new = fmaxf(m_run[i], ceilf(mx));
             const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
             const float alpha = exp2f(m_run[i] - m_safe);
             m_run[i] = m_new;

@@ -5,9 +5,10 @@ import tidar_inputs as TI
 
 
 def near_tie_mismatches(got_tokens, oracle_logits, tol):
-    """Compare chosen tokens row by row with the oracle's argmax.  A mismatch is excused only when the
-    oracle's own margin between its top token and the token the device chose is below 2*tol.
-    Returns (n_mismatch, n_unexcused)."""
+    """Compare chosen tokens row by row with the oracle's argmax.  If every device logit is within `tol` of
+    the oracle's, the device can only prefer another token when the oracle's margin between its top token and
+    that token is below 2*tol; callers pass the *measured* maximum logit error as `tol`, so a mismatch on any
+    wider margin is a real error.  Returns (n_mismatch, n_unexcused)."""
     want = oracle_logits.argmax(dim=-1)
     n_mis = n_bad = 0
     for r in range(oracle_logits.shape[0]):

@@ -128,3 +128,28 @@ def test_causal_forward_matches_independent_transformer(shape):
     # the library builds its cos/sin tables in fp32, so agreement stops near 1e-7; a wrong pairing, sign,
     # scale or norm placement shows up at 1e-2 and above
     assert torch.allclose(got, want, atol=1e-6), float((got - want).abs().max())
+
+
+def test_rounded_softmax_numerators_do_not_depend_on_power_of_two_reference():
+    """Reading K: bf16 rounding of 2^(s - ref) is the same for every integral ref (pure exponent shift)."""
+    torch.manual_seed(5)
+    s2 = torch.randn(7, 300, dtype=torch.float64) * 4.0
+    ref = torch.ceil(s2.max(dim=-1, keepdim=True).values)
+    e1 = O.round_bf16(torch.exp2(s2 - ref))
+    e2 = O.round_bf16(torch.exp2(s2 - (ref + 5.0)))
+    assert torch.equal(e1, e2 * 32.0)
+    assert float(e1.max()) <= 1.0 and float(e1.max()) > 0.5
+
+
+def test_rounded_attention_stays_within_bf16_resolution_of_exact():
+    torch.manual_seed(6)
+    k, L, n_q, n_kv, hd = 4, 50, 4, 2, 16
+    R = O.q_len(k)
+    q = torch.randn(R, n_q, hd, dtype=torch.float64)
+    keys = torch.randn(L + R, n_kv, hd, dtype=torch.float64)
+    vals = torch.randn(L + R, n_kv, hd, dtype=torch.float64)
+    mask = O.decode_mask(k, L)
+    exact = O.attention_dense(q, keys, vals, mask)
+    rounded = O.attention_dense(q, keys, vals, mask, round_p=True)
+    err = float((exact - rounded).abs().max())
+    assert 0.0 < err < 2.0 ** -8
