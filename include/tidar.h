@@ -117,7 +117,7 @@ void         tidar_destroy(tidar_ctx *ctx);
 const char  *tidar_strerror(tidar_status s);
 
 /* Bytes of a packed projection matrix with `rows` output features and `cols`
- * input features (rows multiple of 16, cols multiple of 32 in bf16 mode). */
+ * input features (rows multiple of 16, padded to 32; cols multiple of 32 in bf16 mode). */
 size_t       tidar_packed_weight_bytes(int32_t dtype, int32_t rows, int32_t cols);
 
 /*
@@ -126,8 +126,9 @@ size_t       tidar_packed_weight_bytes(int32_t dtype, int32_t rows, int32_t cols
  * dst_tile_offset + t * dst_tile_stride of the destination, so several source
  * matrices can share one destination (Q|K|V, interleaved gate/up).
  * `dst_rows` is the destination's total row count.
- * bf16 layout: [row tile][k step of 32][lane 0..63][8 values], lane = (k/8 % 4)*16 + row%16,
- * i.e. the register image of one MFMA operand; fp32 layout: plain row-major.
+ * bf16 layout: [k step of 16][32-row tile][lane 0..63][8 values], lane = (k/8 % 2)*32 + row%32,
+ * i.e. the register image of one 32x32x16 MFMA operand, k step outermost (destination rows are padded
+ * to a multiple of 32); fp32 layout: plain row-major.
  */
 tidar_status tidar_pack_weight(int32_t dtype, const void *src, int32_t rows, int32_t cols,
                                void *dst, int32_t dst_rows, int32_t dst_tile_offset, int32_t dst_tile_stride,

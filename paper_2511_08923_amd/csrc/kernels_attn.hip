@@ -302,31 +302,43 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
     }
 }
 
-// out[b][r][head][d] = sum_s w_s O_s / sum_s w_s l_s,  w_s = 2^(m_s - max m)
-__global__ __launch_bounds__(128) void attn_combine_kernel(const float *__restrict__ opart,
+// out[row][head][d] = sum_s w_s O_s / sum_s w_s l_s,  w_s = 2^(m_s - max m): exact powers of two, since every
+// split keeps an integral reference.  One block per row; a thread owns 8 head-dim values of one head and writes
+// them as one 16-byte piece, either row-major or in the A-fragment layout of the O projection's input.
+__global__ __launch_bounds__(256) void attn_combine_kernel(const float *__restrict__ opart,
                                                            const float *__restrict__ mpart,
                                                            const float *__restrict__ lpart, int R, int n_q, int n_kv,
-                                                           int splits, bf16_t *__restrict__ out) {
-    int row = blockIdx.x;                 // b * R + r
-    int head = blockIdx.y;
-    int b = row / R, r = row - b * R;
-    int group = n_q / n_kv;
-    int g = head / group, hq = head - g * group;
-    int F = group * R;
-    int f = hq * R + r;
-    size_t base = ((size_t)b * n_kv + g) * splits;
-    float mmax = -INFINITY;
-    for (int s = 0; s < splits; ++s) mmax = fmaxf(mmax, mpart[(base + s) * F + f]);
-    float num = 0.f, den = 0.f;
-    int dd = threadIdx.x;
-    for (int s = 0; s < splits; ++s) {
-        float m = mpart[(base + s) * F + f];
-        if (m == -INFINITY) continue;
-        float wgt = exp2f(m - mmax);
-        num += wgt * opart[((base + s) * F + f) * HD + dd];
-        den += wgt * lpart[(base + s) * F + f];
+                                                           int splits, bf16_t *__restrict__ out, int out_af,
+                                                           ActLayout lay) {
+    const int row = blockIdx.x;                 // b * R + r
+    const int b = row / R, r = row - b * R;
+    const int group = n_q / n_kv;
+    const int F = group * R;
+    for (int item = threadIdx.x; item < n_q * (HD / 8); item += blockDim.x) {
+        const int head = item / (HD / 8), d0 = 8 * (item % (HD / 8));
+        const int g = head / group, hq = head - g * group;
+        const int f = hq * R + r;
+        const size_t base = ((size_t)b * n_kv + g) * splits;
+        float mmax = -INFINITY;
+        for (int sp = 0; sp < splits; ++sp) mmax = fmaxf(mmax, mpart[(base + sp) * F + f]);
+        float num[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, den = 0.f;
+        for (int sp = 0; sp < splits; ++sp) {
+            const float m = mpart[(base + sp) * F + f];
+            if (m == -INFINITY) continue;
+            const float wgt = exp2f(m - mmax);
+            const float *op = opart + ((base + sp) * F + f) * HD + d0;
+            const float4 a = *(const float4 *)op, c = *(const float4 *)(op + 4);
+            num[0] += wgt * a.x; num[1] += wgt * a.y; num[2] += wgt * a.z; num[3] += wgt * a.w;
+            num[4] += wgt * c.x; num[5] += wgt * c.y; num[6] += wgt * c.z; num[7] += wgt * c.w;
+            den += wgt * lpart[(base + sp) * F + f];
+        }
+        const float inv = 1.f / den;
+        bf16x8 o;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = (bf16_t)(num[e] * inv);
+        const size_t idx = out_af ? af_index(row, head * HD + d0, lay) : ((size_t)row * n_q + head) * HD + d0;
+        *(bf16x8 *)(out + idx) = o;
     }
-    out[((size_t)row * n_q + head) * HD + dd] = (bf16_t)(num / den);
 }
 
 }  // namespace
@@ -380,10 +392,9 @@ void launch_attention_bf16(const bf16_t *q, KvView kv, const bf16_t *k_scr, cons
 }
 
 void launch_attention_combine(const float *part, int B, int R, int n_q, int n_kv, int hd, int splits, bf16_t *out,
-                              hipStream_t st) {
+                              int out_af, hipStream_t st) {
     size_t F = (size_t)(n_q / n_kv) * R;
     size_t rows = (size_t)B * n_kv * splits * F;
-    dim3 grid(B * R, n_q);
-    attn_combine_kernel<<<grid, 128, 0, st>>>(part, part + rows * hd, part + rows * hd + rows, R, n_q, n_kv, splits,
-                                              out);
+    attn_combine_kernel<<<B * R, 256, 0, st>>>(part, part + rows * hd, part + rows * hd + rows, R, n_q, n_kv, splits,
+                                               out, out_af, act_layout(B * R));
 }

@@ -1,216 +1,356 @@
-// Skinny bf16 GEMM for the decode step: out[M][N] (fp32) = A[M][K] (bf16) x W[N][K]^T (bf16, packed).
+// Skinny bf16 GEMM of the decode step: out = A[M][K] (bf16) x W[N][K]^T (bf16), fp32 accumulation.
 //
-// M is the step's row count (1 .. 272 per pass), N and K are model dimensions, so every weight byte is used
-// once per step and the kernel is a weight streamer with MFMA attached:
-//   * W lives in HBM as the register image of the MFMA B operand ([16-column tile][32-wide k step][lane][8]),
-//     so a wave's load of one fragment is one fully coalesced 1 KiB read that goes straight to VGPRs.  Each
-//     wave owns its column tiles exclusively: weights never pass through LDS and are never read twice.
-//   * A (small, L2 resident) is staged through LDS once per workgroup and shared by its four waves.
-//   * split-K over blockIdx.y fills the 256 CUs when N alone gives too few workgroups; partial sums go to
-//     out[split][M][N] and are summed in fixed order by the consumer kernel (deterministic, no atomics).
-// MFMA: v_mfma_f32_16x16x32_bf16.  A operand lane l: row l%16, k slots 8*(l/16)..+7;  B operand lane l:
-// column l%16, same k slots;  D lane l register i: row 4*(l/16)+i, column l%16.
+// M is the step's row count (1 .. 272 per pass), N and K are model dimensions: every weight byte is used once
+// per step, so the kernel is a weight streamer with MFMA attached.
+//   * W lives in HBM as the register image of the 32x32x16 MFMA B operand
+//     ([k step of 16][32-column tile][lane][8]); a wave's load of one fragment is one fully coalesced 1 KiB read
+//     that goes straight to VGPRs through a ring many k steps deep.  Weights never pass through LDS.  The k
+//     step is the outer index so that the workgroups, which all advance through K at the same pace, read one
+//     contiguous front of the matrix.
+//   * A lives in memory as the register image of the MFMA A operand (see ActLayout): the slice a workgroup
+//     needs for a chunk of K is one contiguous block and its LDS image reads back conflict-free.
+//   * every load is a raw buffer load: out-of-range tiles, rows and k steps are steered to an out-of-bounds
+//     offset, which the hardware answers with zeros and no memory traffic.  The steady-state loop therefore
+//     has no branches, and the compiler can keep exact in-flight counts (vmcnt(n), not vmcnt(0)) on the ring;
+//     sched_barrier pins each reload right behind the MFMAs that free its slot.
+//   * M <= 32: 16x16x32 MFMA (fewer pad rows), no LDS, no barriers; a wave streams its 32 columns and the A
+//     fragments through two register rings.  M > 32: 32x32x16 MFMA (on gfx950 it issues at twice the rate of
+//     16x16x32: measured 2.2 vs 1.2 PFLOP/s), 4 waves as a 2 x 2 grid (two row halves x two 64-column groups),
+//     A staged through LDS once per workgroup and prefetched into registers ahead of the MFMAs.
+//   * a workgroup always covers 128 columns, and split-K over blockIdx.y works in units of 512 k: the split
+//     count depends on (N, K) only, never on M, so the partial-sum grouping of a row never depends on how many
+//     rows travel with it.
+//   * output: [split][16-column tile][row][16] fp32 (a tile is one contiguous block) or plain row-major for
+//     the LM head; partials are summed in fixed order by the consumer.
+// 16x16x32: A lane l = row l%16, k slots 8*(l/16)..+7; B lane l = column l%16, same k slots; D lane l register i
+// = row 4*(l/16)+i, column l%16.   32x32x16: A lane l = row l%32, k slots 8*(l/32)..+7; B lane l = column l%32;
+// D lane l register i = row 8*(i/4) + 4*(l/32) + i%4, column l%32.
+#include <stdlib.h>
+
 #include "tidar_internal.h"
 
 namespace {
 
-template <int MT> struct GemmCfg;
-template <> struct GemmCfg<1>  { static constexpr int BK = 512; };
-template <> struct GemmCfg<2>  { static constexpr int BK = 256; };
-template <> struct GemmCfg<5>  { static constexpr int BK = 128; };
-template <> struct GemmCfg<9>  { static constexpr int BK = 64; };
-template <> struct GemmCfg<17> { static constexpr int BK = 64; };
+constexpr int SPLIT_UNIT = 512;           // k elements
+constexpr int OOB = 0x7ffffff0;           // byte offset beyond any buffer: the load returns zeros
 
-// PF = weight chunks kept in flight per wave (register ring).
-template <int MT, int NT, int PF>
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t *__restrict__ a, const bf16_t *__restrict__ w,
-                                                        float *__restrict__ out, int M, int N, int K, int splits) {
-    constexpr int BK = GemmCfg<MT>::BK;
-    constexpr int KS = BK / 32;                 // MFMA k steps per chunk
-    constexpr int ROWS = MT * 16;
-    constexpr int LDS_STRIDE = BK + 8;          // bf16 elements; +16 bytes keeps ds_read_b128 conflict free
-    constexpr int PIECES = ROWS * (BK / 8);     // 16-byte pieces per chunk
-    constexpr int STAGE = (PIECES + 255) / 256; // pieces per thread
-    extern __shared__ __attribute__((aligned(16))) unsigned char gemm_smem[];
-    bf16_t (*lds)[ROWS * LDS_STRIDE] = reinterpret_cast<bf16_t (*)[ROWS * LDS_STRIDE]>(gemm_smem);
+__device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void *base, size_t bytes) {
+    // raw buffer (stride 0), 32-bit data format; num_records in bytes
+    return __builtin_amdgcn_make_buffer_rsrc((void *)base, 0, (int)(bytes > 0x7fffffe0ull ? 0x7fffffe0ull : bytes),
+                                             0x00020000);
+}
+__device__ inline bf16x8 buf_load(__amdgpu_buffer_rsrc_t r, int byte_off) {
+    return __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, 0));
+}
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int n_tiles = N / 16, ksteps_total = K / 32;
-    const int m_base = blockIdx.z * ROWS;
-    const int split = blockIdx.y;
-    const int n_chunks = (K + BK - 1) / BK;
-    const int per = (n_chunks + splits - 1) / splits;
-    const int c0 = split * per;
-    const int c1 = min(n_chunks, c0 + per);
-    const int tile0 = (blockIdx.x * 4 + wave) * NT;          // this wave's first column tile
-    const bool wave_active = tile0 < n_tiles;
+struct SplitRange {
+    int q0, q1;   // k steps [q0, q1)
+};
+__device__ inline SplitRange split_range(int K, int splits, int split) {
+    const int units = (K + SPLIT_UNIT - 1) / SPLIT_UNIT;
+    const int per = (units + splits - 1) / splits;
+    SplitRange r;
+    r.q0 = split * per * (SPLIT_UNIT / 32);
+    r.q1 = min(K >> 5, (split + 1) * per * (SPLIT_UNIT / 32));
+    return r;
+}
+
+template <int MTW, int NT>
+__device__ inline void store_tiles(const f32x4 (&acc)[MTW][NT], float *out, int split, int M, int N, int tile0,
+                                   int n_tiles, int mt0, int lane, int out_row_major) {
+    float *o = out + (size_t)split * M * N;
+#pragma unroll
+    for (int mt = 0; mt < MTW; ++mt) {
+        const int row0 = (mt0 + mt) * 16 + (lane >> 4) * 4;
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+            const int tile = tile0 + j;
+            if (tile >= n_tiles) continue;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int row = row0 + i;
+                if (row < M) {
+                    size_t idx = out_row_major ? (size_t)row * N + tile * 16 + (lane & 15)
+                                               : ((size_t)tile * M + row) * 16 + (lane & 15);
+                    o[idx] = acc[mt][j][i];
+                }
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------ M <= 32: register rings only
+template <int MT, int PFK>
+__global__ __launch_bounds__(256) void gemm_bf16_small_kernel(const bf16_t *__restrict__ a,
+                                                              const bf16_t *__restrict__ w, float *__restrict__ out,
+                                                              int M, int N, int K, int splits, int out_row_major) {
+    constexpr int NT = 2;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n_tiles = N >> 4, m_tiles = (M + 15) >> 4;
+    const SplitRange sr = split_range(K, splits, blockIdx.y);
+    const int tile0 = (blockIdx.x * 4 + wave) * NT;
+    if (tile0 >= n_tiles) return;                              // no barriers in this kernel
+    const __amdgpu_buffer_rsrc_t ra = make_rsrc(a, (size_t)(K >> 5) * m_tiles * 1024);
+    const __amdgpu_buffer_rsrc_t rw = make_rsrc(w, (size_t)((N + 31) / 32) * 32 * K * 2);
+    // byte offsets at k step 0; one k step further is n_tiles (resp. m_tiles) KiB on
+    // W is stored for the 32x32x16 form; two of its k steps hold the 32 k of one 16x16x32 step.  Lane (n, g)
+    // of the B operand takes its 8 values from stored k step 2Q + g/2, stored lane (g%2)*32 + 16*half + n:
+    // k slot g then covers k = 32Q + 8g .. +7, the same slots the narrow A layout gives lane group g.
+    const int t32 = (N + 31) >> 5;
+    const int n = lane & 15, g = lane >> 4;
+    int w_off[NT], a_off[MT];
+#pragma unroll
+    for (int j = 0; j < NT; ++j)
+        w_off[j] = (tile0 + j < n_tiles)
+                       ? ((((g >> 1) * t32 + ((tile0 + j) >> 1)) * 64) + (g & 1) * 32 + ((tile0 + j) & 1) * 16 + n) * 16
+                       : OOB;
+#pragma unroll
+    for (int i = 0; i < MT; ++i) a_off[i] = (i < m_tiles) ? (i * 64 + lane) * 16 : OOB;
+    const int w_step = 2 * t32 * 1024, a_step = m_tiles * 1024;
+    auto ld_w = [&](int j, int q) {
+        return buf_load(rw, (q < sr.q1 && w_off[j] != OOB) ? w_off[j] + q * w_step : OOB);
+    };
+    auto ld_a = [&](int i, int q) {
+        return buf_load(ra, (q < sr.q1 && a_off[i] != OOB) ? a_off[i] + q * a_step : OOB);
+    };
 
     f32x4 acc[MT][NT];
 #pragma unroll
     for (int i = 0; i < MT; ++i)
 #pragma unroll
         for (int j = 0; j < NT; ++j) acc[i][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
-
-    // ---- A staging: thread -> (row, 16-byte piece) pairs of the chunk
-    bf16x8 stage[STAGE];
-    auto load_a = [&](int chunk) {
+    bf16x8 wbuf[PFK][NT], abuf[PFK][MT];
 #pragma unroll
-        for (int s = 0; s < STAGE; ++s) {
-            int p = tid + s * 256;
-            int row = p / (BK / 8), piece = p % (BK / 8);
-            int kk = chunk * BK + piece * 8;
-            bf16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
-            if (p < PIECES && m_base + row < M && kk < K)
-                v = *(const bf16x8 *)(a + (size_t)(m_base + row) * K + kk);
-            stage[s] = v;
+    for (int s = 0; s < PFK; ++s) {
+#pragma unroll
+        for (int j = 0; j < NT; ++j) wbuf[s][j] = ld_w(j, sr.q0 + s);
+#pragma unroll
+        for (int i = 0; i < MT; ++i) abuf[s][i] = ld_a(i, sr.q0 + s);
+    }
+    for (int qb = sr.q0; qb < sr.q1; qb += PFK) {
+#pragma unroll
+        for (int s = 0; s < PFK; ++s) {
+#pragma unroll
+            for (int i = 0; i < MT; ++i)
+#pragma unroll
+                for (int j = 0; j < NT; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(abuf[s][i], wbuf[s][j], acc[i][j], 0, 0, 0);
+#pragma unroll
+            for (int j = 0; j < NT; ++j) wbuf[s][j] = ld_w(j, qb + s + PFK);
+#pragma unroll
+            for (int i = 0; i < MT; ++i) abuf[s][i] = ld_a(i, qb + s + PFK);
+            // keep each slot's reload right behind its use: hoisting or sinking it shortens the ring
+            __builtin_amdgcn_sched_barrier(0);
         }
+    }
+    store_tiles<MT, NT>(acc, out, blockIdx.y, M, N, tile0, n_tiles, 0, lane, out_row_major);
+}
+
+// ------------------------------------------------------------------ 32 < M: 32x32x16 MFMA, A through LDS, 2 x 2 waves
+// MTA: 32-row tiles per wave; the workgroup pass covers CTL row tiles (2*MTA, or 9 when MTA is 5: the second
+// row half then repeats a tile whose results are dropped).  Chunk of K = 128 (8 k steps); weight ring 16 k steps.
+template <int MTA>
+__global__ __launch_bounds__(256) void gemm_bf16_large_kernel(const bf16_t *__restrict__ a,
+                                                              const bf16_t *__restrict__ w, float *__restrict__ out,
+                                                              int M, int N, int K, int splits, int out_row_major) {
+    constexpr int NT = 2, KS = 8, PFK = 16;
+    constexpr int CTL = (MTA == 5) ? 9 : 2 * MTA;
+    constexpr int PIECES = CTL * KS * 64;        // 16-byte pieces per chunk
+    constexpr int STAGE = (PIECES + 255) / 256;
+    constexpr int FR = KS * MTA;                 // A fragments a wave consumes per chunk
+    constexpr int AFD = 3;                       // LDS -> register prefetch distance in fragments
+    extern __shared__ __attribute__((aligned(16))) unsigned char gemm_smem[];
+    bf16x8 *lds = reinterpret_cast<bf16x8 *>(gemm_smem);      // [2][KS][CTL][64]
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int mh = wave & 1, ng = wave >> 1;
+    const int t32 = (N + 31) >> 5, m_tiles = (M + 31) >> 5;
+    const int mt_base = blockIdx.z * CTL;
+    const int ct_here = min(CTL, m_tiles - mt_base);
+    const int q_total = K >> 4;                                // k steps of 16
+    const SplitRange sr32 = split_range(K, splits, blockIdx.y);
+    const int q0 = sr32.q0 * 2, q1 = min(sr32.q1 * 2, q_total);
+    const int c0 = q0 / KS, c1 = (q1 + KS - 1) / KS;
+    const int tile0 = (blockIdx.x * 2 + ng) * NT;              // first 32-column tile of this wave
+    const __amdgpu_buffer_rsrc_t ra = make_rsrc(a, (size_t)q_total * m_tiles * 1024);
+    const __amdgpu_buffer_rsrc_t rw = make_rsrc(w, (size_t)t32 * 32 * K * 2);
+
+    int w_off[NT];
+#pragma unroll
+    for (int j = 0; j < NT; ++j) w_off[j] = (tile0 + j < t32) ? ((tile0 + j) * 64 + lane) * 16 : OOB;
+    const int w_step = t32 * 1024;
+    auto ld_w = [&](int j, int q) {
+        return buf_load(rw, (q < q1 && w_off[j] != OOB) ? w_off[j] + q * w_step : OOB);
+    };
+
+    // A staging: piece p = tid + s*256 of the chunk -> (k step, row tile, lane)
+    int a_off[STAGE];
+#pragma unroll
+    for (int s = 0; s < STAGE; ++s) {
+        const int p = tid + s * 256;
+        const int ks = p / (CTL * 64), rem = p % (CTL * 64);
+        const int ct = rem >> 6, ln = rem & 63;
+        a_off[s] = (p < PIECES && ct < ct_here) ? ((ks * m_tiles + mt_base + ct) * 64 + ln) * 16 : OOB;
+    }
+    const int a_chunk_step = KS * m_tiles * 1024;
+    bf16x8 stage[STAGE];
+    auto load_a = [&](int c) {
+#pragma unroll
+        for (int s = 0; s < STAGE; ++s)
+            stage[s] = buf_load(ra, (c < c1 && a_off[s] != OOB) ? a_off[s] + c * a_chunk_step : OOB);
     };
     auto store_a = [&](int buf) {
 #pragma unroll
-        for (int s = 0; s < STAGE; ++s) {
-            int p = tid + s * 256;
-            int row = p / (BK / 8), piece = p % (BK / 8);
-            if (p < PIECES) *(bf16x8 *)(&lds[buf][row * LDS_STRIDE + piece * 8]) = stage[s];
-        }
+        for (int s = 0; s < STAGE; ++s)
+            if (STAGE * 256 == PIECES || tid + s * 256 < PIECES) lds[buf * PIECES + tid + s * 256] = stage[s];
     };
 
-    // ---- W ring: wbuf[slot][nt][ks]
-    bf16x8 wbuf[PF][NT][KS];
-    auto load_w = [&](int slot, int chunk) {
+    f32x16 acc[MTA][NT];
 #pragma unroll
-        for (int j = 0; j < NT; ++j) {
-            int tile = tile0 + j;
+    for (int i = 0; i < MTA; ++i)
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                int q = chunk * KS + ks;
-                bf16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
-                if (tile < n_tiles && q < ksteps_total)
-                    v = *(const bf16x8 *)(w + (((size_t)tile * ksteps_total + q) * 64 + lane) * 8);
-                wbuf[slot][j][ks] = v;
-            }
-        }
-    };
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    if (c0 < c1) {
-        load_a(c0);
+    bf16x8 wbuf[PFK][NT];
+    load_a(c0);
 #pragma unroll
-        for (int i = 0; i < PF; ++i)
-            if (c0 + i < c1 && wave_active) load_w(i, c0 + i);
-        store_a(0);
-    }
+    for (int s = 0; s < PFK; ++s)
+#pragma unroll
+        for (int j = 0; j < NT; ++j) wbuf[s][j] = ld_w(j, q0 + s);
+    store_a(0);
     __syncthreads();
 
-    const int a_lane_off = (lane & 15) * LDS_STRIDE + (lane >> 4) * 8;
-    for (int cb = c0; cb < c1; cb += PF) {
+    // fragment f of a chunk = (k step f / MTA, row tile f % MTA of this wave's half, clamped to a real tile)
+    int frag_off[MTA];
 #pragma unroll
-        for (int i = 0; i < PF; ++i) {
-            const int c = cb + i;
-            if (c < c1) {
-                const int buf = (c - c0) & 1;
-                if (c + 1 < c1) load_a(c + 1);
-                if (wave_active) {
+    for (int mt = 0; mt < MTA; ++mt) frag_off[mt] = min(mh * MTA + mt, CTL - 1) * 64 + lane;
+    auto lds_frag = [&](int buf, int f) { return lds[buf * PIECES + (f / MTA) * CTL * 64 + frag_off[f % MTA]]; };
+
+    for (int cb = c0; cb < c1; cb += 2) {
 #pragma unroll
-                    for (int ks = 0; ks < KS; ++ks) {
+        for (int ci = 0; ci < 2; ++ci) {          // two chunks = one revolution of the weight ring
+            const int c = cb + ci;
+            const int buf = ci;                   // chunks alternate buffers starting from buffer 0 at c0
+            load_a(c + 1);
+            __builtin_amdgcn_sched_barrier(0);
+            bf16x8 af[AFD + 1];
 #pragma unroll
-                        for (int mt = 0; mt < MT; ++mt) {
-                            bf16x8 af = *(const bf16x8 *)(&lds[buf][mt * 16 * LDS_STRIDE + a_lane_off + ks * 32]);
+            for (int f = 0; f < AFD; ++f) af[f] = lds_frag(buf, f);
 #pragma unroll
-                            for (int j = 0; j < NT; ++j)
-                                acc[mt][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, wbuf[i][j][ks], acc[mt][j],
-                                                                                     0, 0, 0);
-                        }
-                    }
-                    if (c + PF < c1) load_w(i, c + PF);
+            for (int f = 0; f < FR; ++f) {
+                if (f + AFD < FR) af[(f + AFD) % (AFD + 1)] = lds_frag(buf, f + AFD);
+                const int ks = f / MTA, mt = f % MTA;
+                const int slot = ci * KS + ks;
+#pragma unroll
+                for (int j = 0; j < NT; ++j)
+                    acc[mt][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[f % (AFD + 1)], wbuf[slot][j], acc[mt][j],
+                                                                         0, 0, 0);
+                if (mt == MTA - 1) {              // this k step's ring slot is free again
+#pragma unroll
+                    for (int j = 0; j < NT; ++j) wbuf[slot][j] = ld_w(j, c * KS + ks + PFK);
                 }
-                if (c + 1 < c1) store_a(buf ^ 1);
-                __syncthreads();
+                __builtin_amdgcn_sched_barrier(0);    // pin the order: LDS prefetch, MFMAs, ring reload
             }
+            store_a(buf ^ 1);
+            __syncthreads();
         }
     }
 
-    // ---- epilogue: D lane l reg i -> row 4*(l/16)+i, column l%16
-    if (wave_active) {
-        float *o = out + (size_t)split * M * N;
+    // ---- epilogue: D lane l register i = row 8*(i/4) + 4*(l/32) + i%4, column l%32
+    float *o = out + (size_t)blockIdx.y * M * N;
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
+    for (int mt = 0; mt < MTA; ++mt) {
+        const int tile_r = mh * MTA + mt;
+        if (tile_r >= ct_here) continue;          // also drops the repeated tile
 #pragma unroll
-            for (int j = 0; j < NT; ++j) {
-                int tile = tile0 + j;
-                if (tile >= n_tiles) continue;
-                int col = tile * 16 + (lane & 15);
+        for (int j = 0; j < NT; ++j) {
+            const int col = (tile0 + j) * 32 + (lane & 31);
+            if (col >= N) continue;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    int row = m_base + mt * 16 + (lane >> 4) * 4 + i;
-                    if (row < M) o[(size_t)row * N + col] = acc[mt][j][i];
+            for (int e = 0; e < 16; ++e) {
+                const int row = (mt_base + tile_r) * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+                if (row < M) {
+                    size_t idx = out_row_major ? (size_t)row * N + col : ((size_t)(col >> 4) * M + row) * 16 + (col & 15);
+                    o[idx] = acc[mt][j][e];
                 }
             }
         }
     }
 }
 
-template <int MT, int NT>
-void launch_cfg(const bf16_t *a, const bf16_t *w, float *out, int M, int N, int K, const GemmPlan &p, hipStream_t st) {
-    int n_tiles = N / 16;
-    dim3 grid((n_tiles + 4 * NT - 1) / (4 * NT), p.splits, p.m_chunks);
-    constexpr int PF = (NT == 4) ? 2 : ((MT >= 9) ? 4 : 2);
-    constexpr int BK = GemmCfg<MT>::BK;
-    constexpr size_t SMEM = (size_t)2 * MT * 16 * (BK + 8) * sizeof(bf16_t);
+template <int MT, int PFK>
+void launch_small(const bf16_t *a, const bf16_t *w, float *out, int M, int N, int K, const GemmPlan &p, int row_major,
+                  hipStream_t st) {
+    dim3 grid((N + 127) / 128, p.splits, 1);
+    gemm_bf16_small_kernel<MT, PFK><<<grid, 256, 0, st>>>(a, w, out, M, N, K, p.splits, row_major);
+}
+
+template <int MTA>
+void launch_large(const bf16_t *a, const bf16_t *w, float *out, int M, int N, int K, const GemmPlan &p, int row_major,
+                  hipStream_t st) {
+    constexpr int CTL = (MTA == 5) ? 9 : 2 * MTA;
+    int m_tiles = (M + 31) / 32;
+    dim3 grid((N + 127) / 128, p.splits, (m_tiles + CTL - 1) / CTL);
+    constexpr size_t SMEM = (size_t)2 * CTL * 8 * 1024;
     static bool attr_set = false;          // LDS above 64 KiB has to be granted per kernel
     if (!attr_set) {
-        (void)hipFuncSetAttribute((const void *)gemm_bf16_kernel<MT, NT, PF>,
+        (void)hipFuncSetAttribute((const void *)gemm_bf16_large_kernel<MTA>,
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)SMEM);
         attr_set = true;
     }
-    gemm_bf16_kernel<MT, NT, PF><<<grid, 256, SMEM, st>>>(a, w, out, M, N, K, p.splits);
-}
-
-template <int MT>
-void launch_mt(const bf16_t *a, const bf16_t *w, float *out, int M, int N, int K, const GemmPlan &p, hipStream_t st) {
-    if (p.nt == 1) launch_cfg<MT, 1>(a, w, out, M, N, K, p, st);
-    else if (p.nt == 2 || MT < 9) launch_cfg<MT, 2>(a, w, out, M, N, K, p, st);
-    else if constexpr (MT >= 9) launch_cfg<MT, 4>(a, w, out, M, N, K, p, st);
+    gemm_bf16_large_kernel<MTA><<<grid, 256, SMEM, st>>>(a, w, out, M, N, K, p.splits, row_major);
 }
 
 }  // namespace
 
+// Every configuration covers 128 columns per workgroup, so the tile count, and with it the split-K plan,
+// depends on (N, K) only.
 GemmPlan plan_gemm_bf16(int M, int N, int K, bool force_single_split) {
     GemmPlan p;
-    int m_tiles = (M + 15) / 16;
-    if (m_tiles <= 1) p.mt = 1;
-    else if (m_tiles <= 2) p.mt = 2;
-    else if (m_tiles <= 5) p.mt = 5;
-    else if (m_tiles <= 9) p.mt = 9;
-    else p.mt = 17;
-    p.m_chunks = (m_tiles + p.mt - 1) / p.mt;
-    p.bk = p.mt == 1 ? 512 : p.mt == 2 ? 256 : p.mt == 5 ? 128 : 64;
-    int n_tiles = N / 16;
-    // columns per workgroup: wide enough that A's L2 traffic stays a small multiple of the weight stream,
-    // narrow enough that split-K partials stay small
-    p.nt = (p.mt >= 9) ? 2 : 1;
-    if (n_tiles >= 4 * 4 * 512) p.nt = (p.mt >= 9) ? 4 : 2;     // very wide N (LM head)
-    if (p.mt < 9 && p.nt > 2) p.nt = 2;
-    int wgs = (n_tiles + 4 * p.nt - 1) / (4 * p.nt);
-    int n_chunks = (K + p.bk - 1) / p.bk;
-    int splits = 1;
-    if (!force_single_split && wgs * p.m_chunks < 224) {
-        splits = (256 + wgs * p.m_chunks - 1) / (wgs * p.m_chunks);
-        if (splits > n_chunks) splits = n_chunks;
-        if (splits > 16) splits = 16;
-        // avoid empty trailing splits
-        int per = (n_chunks + splits - 1) / splits;
-        splits = (n_chunks + per - 1) / per;
+    if (M <= 32) {
+        p.mt = M <= 16 ? 1 : 2;                  // 16-row tiles per wave (narrow kernel)
+        p.m_chunks = 1;
+    } else {
+        int t = (M + 31) / 32;                   // 32-row tiles
+        p.mt = t <= 4 ? 2 : t <= 6 ? 3 : 5;      // per wave (wide kernel)
+        int ctl = p.mt == 5 ? 9 : 2 * p.mt;
+        p.m_chunks = (t + ctl - 1) / ctl;
     }
-    p.splits = splits < 1 ? 1 : splits;
+    p.nt = 2;
+    p.bk = 128;
+    int wgs = (N + 127) / 128;
+    int units = (K + SPLIT_UNIT - 1) / SPLIT_UNIT;
+    int splits = 1;
+    if (!force_single_split && wgs < 224) {
+        splits = (256 + wgs / 2) / wgs;          // nearest count that brings the grid to about one wave of CUs
+        if (splits > units) splits = units;
+        if (splits < 1) splits = 1;
+        int per = (units + splits - 1) / splits;
+        splits = (units + per - 1) / per;        // drop empty trailing splits
+    }
+    if (const char *e = getenv("TIDAR_GEMM_SPLITS")) {   // tuning override for sweeps (unset in normal use)
+        int v = atoi(e);
+        if (v >= 1 && v <= units && !force_single_split) {
+            int per = (units + v - 1) / v;
+            splits = (units + per - 1) / per;
+        }
+    }
+    p.splits = splits;
     return p;
 }
 
 void launch_gemm_bf16(const bf16_t *a, const bf16_t *w, float *out, int M, int N, int K, const GemmPlan &p,
-                      hipStream_t st) {
-    switch (p.mt) {
-        case 1: launch_mt<1>(a, w, out, M, N, K, p, st); break;
-        case 2: launch_mt<2>(a, w, out, M, N, K, p, st); break;
-        case 5: launch_mt<5>(a, w, out, M, N, K, p, st); break;
-        case 9: launch_mt<9>(a, w, out, M, N, K, p, st); break;
-        default: launch_mt<17>(a, w, out, M, N, K, p, st); break;
+                      int out_row_major, hipStream_t st) {
+    if (M <= 32) {
+        if (p.mt == 1) launch_small<1, 16>(a, w, out, M, N, K, p, out_row_major, st);
+        else launch_small<2, 8>(a, w, out, M, N, K, p, out_row_major, st);
+    } else if (p.mt == 2) {
+        launch_large<2>(a, w, out, M, N, K, p, out_row_major, st);
+    } else if (p.mt == 3) {
+        launch_large<3>(a, w, out, M, N, K, p, out_row_major, st);
+    } else {
+        launch_large<5>(a, w, out, M, N, K, p, out_row_major, st);
     }
 }

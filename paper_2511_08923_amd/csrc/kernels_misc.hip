@@ -12,6 +12,16 @@ template <typename T> __device__ inline T from_f(float v);
 template <> __device__ inline float from_f<float>(float v) { return v; }
 template <> __device__ inline bf16_t from_f<bf16_t>(float v) { return (bf16_t)v; }   // round to nearest even
 
+template <typename T> __device__ inline void store4(T *p, float a, float b, float c, float d);
+template <> __device__ inline void store4<float>(float *p, float a, float b, float c, float d) {
+    *(float4 *)p = make_float4(a, b, c, d);
+}
+template <> __device__ inline void store4<bf16_t>(bf16_t *p, float a, float b, float c, float d) {
+    typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+    bf16x4 v = {(bf16_t)a, (bf16_t)b, (bf16_t)c, (bf16_t)d};
+    *(bf16x4 *)p = v;
+}
+
 __device__ inline float wave_sum(float v) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
@@ -24,21 +34,21 @@ __device__ inline float wave_max(float v) {
 }
 
 // ------------------------------------------------------------------ weight packing
-// bf16: dst[((tile * (K/32) + q) * 64 + lane) * 8 + j] = src[(16 t + lane%16) * K + 32 q + 8 (lane/16) + j]
+// bf16 destination: [k step of 16][32-row tile][lane][8], lane = (k/8 % 2) * 32 + row % 32: the register image
+// of the 32x32x16 MFMA B operand.  The k step is outermost: all workgroups of a GEMM advance through K together,
+// so at any moment they read one contiguous front of the matrix, which spreads over every HBM channel.
+// Source row r lands in destination row 16 * (tile_off + (r / 16) * tile_stride) + r % 16.
 __global__ void pack_bf16_kernel(const bf16_t *__restrict__ src, int rows, int K, bf16_t *__restrict__ dst,
-                                 int tile_off, int tile_stride) {
-    int ksteps = K / 32;
-    size_t n_frag = (size_t)(rows / 16) * ksteps * 64;          // one 16-byte fragment piece per index
-    for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < n_frag;
+                                 int dst_tiles32, int tile_off, int tile_stride) {
+    const int k8 = K / 8;
+    size_t n = (size_t)rows * k8;                               // one 16-byte piece per index
+    for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < n;
          idx += (size_t)gridDim.x * blockDim.x) {
-        int lane = (int)(idx & 63);
-        size_t tq = idx >> 6;
-        int q = (int)(tq % ksteps);
-        int t = (int)(tq / ksteps);
-        const bf16_t *s = src + (size_t)(16 * t + (lane & 15)) * K + 32 * q + 8 * (lane >> 4);
-        size_t dt = (size_t)(tile_off + t * tile_stride);
-        bf16_t *o = dst + ((dt * ksteps + q) * 64 + lane) * 8;
-        *(bf16x8 *)o = *(const bf16x8 *)s;
+        int r = (int)(idx / k8);
+        int k = 8 * (int)(idx % k8);
+        int rd = 16 * (tile_off + (r >> 4) * tile_stride) + (r & 15);
+        size_t o = ((((size_t)(k >> 4) * dst_tiles32 + (rd >> 5)) * 64) + ((k >> 3) & 1) * 32 + (rd & 31)) * 8;
+        *(bf16x8 *)(dst + o) = *(const bf16x8 *)(src + (size_t)r * K + k);
     }
 }
 
@@ -83,66 +93,89 @@ __global__ void embed_rows_kernel(const T *__restrict__ embed, const int32_t *__
 }
 
 // ------------------------------------------------------------------ residual add (split-K partials) + RMSNorm
+// One block per output row.  part: tiled GEMM output over M_all rows; out: A-fragment layout over the selected rows.
 template <typename T>
-__global__ void rmsnorm_kernel(float *__restrict__ x, const float *__restrict__ part, int S, size_t part_stride,
-                               const T *__restrict__ gain, float eps, int R, int row0, int d_model,
-                               T *__restrict__ out) {
-    int Rh = R - row0;
-    int b = blockIdx.x / Rh;
-    int o = blockIdx.x - b * Rh;
-    size_t row = (size_t)b * R + row0 + o;
-    float *xr = x + row * d_model;
+__global__ __launch_bounds__(256) void rmsnorm_kernel(float *__restrict__ x, const float *__restrict__ part, int S,
+                                                      size_t split_stride, const T *__restrict__ gain, float eps,
+                                                      int R, int row0, int d_model, int M_all, T *__restrict__ out,
+                                                      ActLayout lay) {
+    const int Rh = R - row0;
+    const int b = blockIdx.x / Rh;
+    const int o = blockIdx.x - b * Rh;
+    const int row = b * R + row0 + o;
+    float *xr = x + (size_t)row * d_model;
     float ss = 0.f;
-    for (int c = threadIdx.x; c < d_model; c += blockDim.x) {
-        float v = xr[c];
-        for (int s = 0; s < S; ++s) v += part[(size_t)s * part_stride + row * d_model + c];
-        if (S > 0) xr[c] = v;
-        ss += v * v;
+    for (int c = 4 * threadIdx.x; c < d_model; c += 4 * blockDim.x) {
+        float4 v = *(const float4 *)(xr + c);
+        if (S > 0) {
+            const float *pp = part + pt_index(c, row, M_all);
+            for (int sp = 0; sp < S; ++sp) {
+                float4 q = *(const float4 *)(pp + (size_t)sp * split_stride);
+                v.x += q.x; v.y += q.y; v.z += q.z; v.w += q.w;
+            }
+            *(float4 *)(xr + c) = v;
+        }
+        ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
     }
-    __shared__ float red[16];
+    __shared__ float red[4];
     ss = wave_sum(ss);
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
     __syncthreads();
-    float tot = 0.f;
-    for (int w = 0; w < (int)(blockDim.x >> 6); ++w) tot += red[w];
-    float rs = rsqrtf(tot / (float)d_model + eps);
-    T *orow = out + (size_t)blockIdx.x * d_model;
-    for (int c = threadIdx.x; c < d_model; c += blockDim.x) orow[c] = from_f<T>(xr[c] * rs * to_f<T>(gain[c]));
+    const float tot = red[0] + red[1] + red[2] + red[3];
+    const float rs = rsqrtf(tot / (float)d_model + eps);
+    for (int c = 4 * threadIdx.x; c < d_model; c += 4 * blockDim.x) {
+        float4 v = *(const float4 *)(xr + c);          // this thread's own writes
+        store4<T>(out + af_index(blockIdx.x, c, lay), v.x * rs * to_f<T>(gain[c]), v.y * rs * to_f<T>(gain[c + 1]),
+                  v.z * rs * to_f<T>(gain[c + 2]), v.w * rs * to_f<T>(gain[c + 3]));
+    }
 }
 
 // ------------------------------------------------------------------ RoPE + K/V placement
-// One block per row.  qkv_part: [S][M][q_dim + 2 kv_dim] fp32.  Q rows -> q_out [M][q_dim];
+// One block per row.  qkv_part: tiled GEMM output, [S] x (q_dim + 2 kv_dim) columns.  Q rows -> q_out [M][q_dim];
 // K/V of causal rows -> cache at position L + r; K/V of mask rows -> scratch tiles
 // k_scr [B][n_kv][n_mtiles][16][hd], v_scr [B][n_kv][n_mtiles][hd][16].
 template <typename T>
-__global__ void rope_kv_kernel(const float *__restrict__ part, int S, size_t part_stride,
-                               const float *__restrict__ rope_cs, const int32_t *__restrict__ prefix_len, RowDesc d,
-                               int n_q, KvView kv, T *__restrict__ q_out, T *__restrict__ k_scr,
-                               T *__restrict__ v_scr) {
-    int row = blockIdx.x;
-    int b = row / d.R;
-    int r = row - b * d.R;
-    int hd = kv.hd, half = hd / 2, n_kv = kv.n_kv;
-    int q_dim = n_q * hd, kv_dim = n_kv * hd, width = q_dim + 2 * kv_dim;
+__global__ __launch_bounds__(256) void rope_kv_kernel(const float *__restrict__ part, int S, size_t split_stride,
+                                                      const float *__restrict__ rope_cs,
+                                                      const int32_t *__restrict__ prefix_len, RowDesc d, int n_q,
+                                                      int M_all, KvView kv, T *__restrict__ q_out,
+                                                      T *__restrict__ k_scr, T *__restrict__ v_scr) {
+    const int row = blockIdx.x;
+    const int b = row / d.R;
+    const int r = row - b * d.R;
+    const int hd = kv.hd, half = hd / 2, n_kv = kv.n_kv;
+    const int q_dim = n_q * hd, kv_dim = n_kv * hd;
+    const int per_head = half / 4;                   // groups of four rotation pairs
     const float *cs = rope_cs + (size_t)row * half * 2;
-    auto val = [&](int col) {
-        float v = 0.f;
-        for (int s = 0; s < S; ++s) v += part[(size_t)s * part_stride + (size_t)row * width + col];
+    auto val4 = [&](int col) {
+        const float *pp = part + pt_index(col, row, M_all);
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int sp = 0; sp < S; ++sp) {
+            float4 q = *(const float4 *)(pp + (size_t)sp * split_stride);
+            v.x += q.x; v.y += q.y; v.z += q.z; v.w += q.w;
+        }
         return v;
     };
-    // Q: rotate pairs (i, i + half)
-    for (int idx = threadIdx.x; idx < n_q * half; idx += blockDim.x) {
-        int h = idx / half, i = idx - h * half;
-        float a = val(h * hd + i), bb = val(h * hd + i + half);
-        float c = cs[2 * i], s = cs[2 * i + 1];
-        q_out[(size_t)row * q_dim + h * hd + i] = from_f<T>(a * c - bb * s);
-        q_out[(size_t)row * q_dim + h * hd + i + half] = from_f<T>(bb * c + a * s);
+    auto rotate = [&](float4 a, float4 bb, int i, float4 &lo, float4 &hi) {
+        float4 c0 = *(const float4 *)(cs + 2 * i), c1 = *(const float4 *)(cs + 2 * i + 4);   // (cos,sin) x 4
+        lo = make_float4(a.x * c0.x - bb.x * c0.y, a.y * c0.z - bb.y * c0.w, a.z * c1.x - bb.z * c1.y,
+                         a.w * c1.z - bb.w * c1.w);
+        hi = make_float4(bb.x * c0.x + a.x * c0.y, bb.y * c0.z + a.y * c0.w, bb.z * c1.x + a.z * c1.y,
+                         bb.w * c1.z + a.w * c1.w);
+    };
+    for (int idx = threadIdx.x; idx < n_q * per_head; idx += blockDim.x) {
+        int h = idx / per_head, i = 4 * (idx - h * per_head);
+        float4 lo, hi;
+        rotate(val4(h * hd + i), val4(h * hd + i + half), i, lo, hi);
+        T *qo = q_out + (size_t)row * q_dim + h * hd + i;
+        store4<T>(qo, lo.x, lo.y, lo.z, lo.w);
+        store4<T>(qo + half, hi.x, hi.y, hi.z, hi.w);
     }
     // destination of this row's K/V
-    bool causal = r < d.nc;
-    int L = prefix_len[d.seq_base + b];
+    const bool causal = r < d.nc;
+    const int L = prefix_len[d.seq_base + b];
     int page = 0, slot = 0, mt = 0;
-    int n_mtiles = (d.nb * d.bl + 15) / 16;
+    const int n_mtiles = (d.nb * d.bl + 15) / 16;
     if (causal) {
         int p = L + r;
         page = kv.page_table[(size_t)(d.seq_base + b) * kv.pages_per_seq + (p >> 4)];
@@ -154,23 +187,27 @@ __global__ void rope_kv_kernel(const float *__restrict__ part, int S, size_t par
     }
     T *kp = (T *)kv.k_pages;
     T *vp = (T *)kv.v_pages;
-    for (int idx = threadIdx.x; idx < n_kv * half; idx += blockDim.x) {
-        int h = idx / half, i = idx - h * half;
-        float a = val(q_dim + h * hd + i), bb = val(q_dim + h * hd + i + half);
-        float c = cs[2 * i], s = cs[2 * i + 1];
-        T k0 = from_f<T>(a * c - bb * s), k1 = from_f<T>(bb * c + a * s);
-        T v0 = from_f<T>(val(q_dim + kv_dim + h * hd + i)), v1 = from_f<T>(val(q_dim + kv_dim + h * hd + i + half));
+    for (int idx = threadIdx.x; idx < n_kv * per_head; idx += blockDim.x) {
+        int h = idx / per_head, i = 4 * (idx - h * per_head);
+        float4 lo, hi;
+        rotate(val4(q_dim + h * hd + i), val4(q_dim + h * hd + i + half), i, lo, hi);
+        float4 v0 = val4(q_dim + kv_dim + h * hd + i), v1 = val4(q_dim + kv_dim + h * hd + i + half);
+        T *kdst, *vdst;            // K: [slot][hd] contiguous in d;  V: [d][16] strided by 16 in d
         if (causal) {
-            kp[k_page_offset(kv, page, h, slot, i)] = k0;
-            kp[k_page_offset(kv, page, h, slot, i + half)] = k1;
-            vp[v_page_offset(kv, page, h, slot, i)] = v0;
-            vp[v_page_offset(kv, page, h, slot, i + half)] = v1;
+            kdst = kp + k_page_offset(kv, page, h, slot, 0);
+            vdst = vp + v_page_offset(kv, page, h, slot, 0);
         } else {
             size_t tile = ((size_t)b * n_kv + h) * n_mtiles + mt;
-            k_scr[(tile * 16 + slot) * hd + i] = k0;
-            k_scr[(tile * 16 + slot) * hd + i + half] = k1;
-            v_scr[(tile * hd + i) * 16 + slot] = v0;
-            v_scr[(tile * hd + i + half) * 16 + slot] = v1;
+            kdst = k_scr + (tile * 16 + slot) * hd;
+            vdst = v_scr + tile * hd * 16 + slot;
+        }
+        store4<T>(kdst + i, lo.x, lo.y, lo.z, lo.w);
+        store4<T>(kdst + i + half, hi.x, hi.y, hi.z, hi.w);
+        const float vv0[4] = {v0.x, v0.y, v0.z, v0.w}, vv1[4] = {v1.x, v1.y, v1.z, v1.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            vdst[(size_t)(i + e) * 16] = from_f<T>(vv0[e]);
+            vdst[(size_t)(i + half + e) * 16] = from_f<T>(vv1[e]);
         }
     }
 }
@@ -214,22 +251,27 @@ __global__ void place_kv_kernel(const T *__restrict__ k_new, const T *__restrict
 }
 
 // ------------------------------------------------------------------ SwiGLU over interleaved gate/up columns
+// part: tiled GEMM output with 2*d_ff columns (tile 2t = gate, 2t+1 = up); out: A-fragment layout, K = d_ff.
 template <typename T>
-__global__ void swiglu_kernel(const float *__restrict__ part, int S, size_t part_stride, int M, int d_ff,
-                              T *__restrict__ out) {
-    size_t n = (size_t)M * d_ff;
+__global__ void swiglu_kernel(const float *__restrict__ part, int S, size_t split_stride, int M, int d_ff,
+                              T *__restrict__ out, ActLayout lay) {
+    const int per_row = d_ff / 4;
+    size_t n = (size_t)M * per_row;
     for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < n; idx += (size_t)gridDim.x * blockDim.x) {
-        size_t row = idx / d_ff;
-        int f = (int)(idx - row * d_ff);
-        size_t gcol = (size_t)32 * (f >> 4) + (f & 15);
-        size_t base = row * (size_t)(2 * d_ff) + gcol;
-        float g = 0.f, u = 0.f;
-        for (int s = 0; s < S; ++s) {
-            g += part[(size_t)s * part_stride + base];
-            u += part[(size_t)s * part_stride + base + 16];
+        // consecutive threads walk down the rows of one column group: the tiled layout is row-contiguous
+        int row = (int)(idx % M);
+        int f = 4 * (int)(idx / M);
+        const float *pg = part + pt_index(32 * (f >> 4) + (f & 15), row, M);
+        const float *pu = part + pt_index(32 * (f >> 4) + 16 + (f & 15), row, M);
+        float4 g = make_float4(0.f, 0.f, 0.f, 0.f), u = g;
+        for (int sp = 0; sp < S; ++sp) {
+            float4 a = *(const float4 *)(pg + (size_t)sp * split_stride);
+            float4 c = *(const float4 *)(pu + (size_t)sp * split_stride);
+            g.x += a.x; g.y += a.y; g.z += a.z; g.w += a.w;
+            u.x += c.x; u.y += c.y; u.z += c.z; u.w += c.w;
         }
-        float act = g / (1.f + __expf(-g));
-        out[idx] = from_f<T>(act * u);
+        store4<T>(out + af_index(row, f, lay), g.x / (1.f + __expf(-g.x)) * u.x, g.y / (1.f + __expf(-g.y)) * u.y,
+                  g.z / (1.f + __expf(-g.z)) * u.z, g.w / (1.f + __expf(-g.w)) * u.w);
     }
 }
 
@@ -331,11 +373,28 @@ __global__ void finish_prefill_kernel(const int32_t *__restrict__ y, int k, int 
     }
 }
 
-__global__ void sum_partials_kernel(const float *__restrict__ part, int S, size_t stride, float *__restrict__ out) {
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < stride; i += (size_t)gridDim.x * blockDim.x) {
+// plain row-major [M][K] -> A-fragment layout (8 elements per thread)
+template <typename T>
+__global__ void pack_act_kernel(const T *__restrict__ src, int M, int K, T *__restrict__ dst, ActLayout lay) {
+    size_t n = (size_t)M * (K / 8);
+    for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < n; idx += (size_t)gridDim.x * blockDim.x) {
+        int row = (int)(idx / (K / 8));
+        int k = 8 * (int)(idx % (K / 8));
+        const T *sp = src + (size_t)row * K + k;
+        T *dp = dst + af_index(row, k, lay);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) dp[j] = sp[j];
+    }
+}
+
+// tiled partial sums [S][N/16][M][16] -> plain row-major [M][N]
+__global__ void untile_sum_kernel(const float *__restrict__ part, int S, int M, int N, float *__restrict__ out) {
+    size_t n = (size_t)M * N;
+    for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < n; idx += (size_t)gridDim.x * blockDim.x) {
+        int row = (int)(idx / N), col = (int)(idx % N);
         float v = 0.f;
-        for (int s = 0; s < S; ++s) v += part[(size_t)s * stride + i];
-        out[i] = v;
+        for (int sp = 0; sp < S; ++sp) v += part[(size_t)sp * n + pt_index(col, row, M)];
+        out[idx] = v;
     }
 }
 
@@ -344,18 +403,21 @@ __global__ void set_i32_kernel(int32_t *p, int n, int32_t v) {
     if (i < n) p[i] = v;
 }
 
-// ------------------------------------------------------------------ fp32 GEMM (plain ALU): out[M][N] = a[M][K] w[N][K]^T
+// ------------------------------------------------------------------ fp32 GEMM (plain ALU)
+// a: A-fragment layout (fp32 elements), w: row-major [N][K], out: tiled or row-major.
 __global__ __launch_bounds__(256) void gemm_f32_kernel(const float *__restrict__ a, const float *__restrict__ w,
-                                                       float *__restrict__ out, int M, int N, int K) {
+                                                       float *__restrict__ out, int M, int N, int K,
+                                                       int out_row_major) {
     __shared__ float As[16][33];
     __shared__ float Ws[64][33];
-    int n0 = blockIdx.x * 64, m0 = blockIdx.y * 16;
-    int tc = threadIdx.x & 63, tr = threadIdx.x >> 6;      // column, row group (4 rows each)
+    const int n0 = blockIdx.x * 64, m0 = blockIdx.y * 16;
+    const int tc = threadIdx.x & 63, tr = threadIdx.x >> 6;      // column, row group (4 rows each)
+    const ActLayout lay = act_layout(M);
     float acc[4] = {0.f, 0.f, 0.f, 0.f};
     for (int k0 = 0; k0 < K; k0 += 32) {
         for (int i = threadIdx.x; i < 16 * 32; i += 256) {
             int r = i >> 5, c = i & 31;
-            As[r][c] = (m0 + r < M && k0 + c < K) ? a[(size_t)(m0 + r) * K + k0 + c] : 0.f;
+            As[r][c] = (m0 + r < M && k0 + c < K) ? a[af_index(m0 + r, k0 + c, lay)] : 0.f;
         }
         for (int i = threadIdx.x; i < 64 * 32; i += 256) {
             int r = i >> 5, c = i & 31;
@@ -371,8 +433,8 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float *__restrict__
         __syncthreads();
     }
     for (int i = 0; i < 4; ++i) {
-        int m = m0 + tr * 4 + i;
-        if (m < M && n0 + tc < N) out[(size_t)m * N + n0 + tc] = acc[i];
+        int m = m0 + tr * 4 + i, n = n0 + tc;
+        if (m < M && n < N) out[out_row_major ? (size_t)m * N + n : pt_index(n, m, M)] = acc[i];
     }
 }
 
@@ -382,7 +444,7 @@ __global__ __launch_bounds__(64) void attention_f32_kernel(const float *__restri
                                                            const float *__restrict__ k_scr,
                                                            const float *__restrict__ v_scr,
                                                            const int32_t *__restrict__ prefix_len, RowDesc d, int n_q,
-                                                           float *__restrict__ out) {
+                                                           float *__restrict__ out, int out_af, ActLayout lay) {
     int row = blockIdx.x;                  // b * R + r
     int head = blockIdx.y;
     int b = row / d.R, r = row - b * d.R;
@@ -453,8 +515,11 @@ __global__ __launch_bounds__(64) void attention_f32_kernel(const float *__restri
         __syncthreads();
     }
     float inv = 1.f / l_run;
-    if (lane < hd) out[((size_t)row * n_q + head) * hd + lane] = o0 * inv;
-    if (lane + 64 < hd) out[((size_t)row * n_q + head) * hd + lane + 64] = o1 * inv;
+    auto oidx = [&](int dd) {
+        return out_af ? af_index(row, head * hd + dd, lay) : ((size_t)row * n_q + head) * hd + dd;
+    };
+    if (lane < hd) out[oidx(lane)] = o0 * inv;
+    if (lane + 64 < hd) out[oidx(lane + 64)] = o1 * inv;
 }
 
 inline int grid_for(size_t n, int block, int cap = 4096) {
@@ -464,12 +529,12 @@ inline int grid_for(size_t n, int block, int cap = 4096) {
 
 }  // namespace
 
-void launch_pack_weight(int dtype, const void *src, int rows, int cols, void *dst, int tile_off, int tile_stride,
-                        hipStream_t st) {
+void launch_pack_weight(int dtype, const void *src, int rows, int cols, void *dst, int dst_rows, int tile_off,
+                        int tile_stride, hipStream_t st) {
     if (dtype == TIDAR_BF16) {
-        size_t n = (size_t)(rows / 16) * (cols / 32) * 64;
+        size_t n = (size_t)rows * (cols / 8);
         pack_bf16_kernel<<<grid_for(n, 256, 65536), 256, 0, st>>>((const bf16_t *)src, rows, cols, (bf16_t *)dst,
-                                                                   tile_off, tile_stride);
+                                                                   (dst_rows + 31) / 32, tile_off, tile_stride);
     } else {
         size_t n = (size_t)rows * cols;
         pack_f32_kernel<<<grid_for(n, 256, 65536), 256, 0, st>>>((const float *)src, rows, cols, (float *)dst,
@@ -489,31 +554,47 @@ void launch_embed_rows(int dtype, const void *embed, const int32_t *tokens, int 
                                                         d_model, mask_id, hd, rope_base, x, pos_out, rope_cs);
 }
 
-void launch_rmsnorm(int dtype, float *x, const float *part, int S, size_t part_stride, const void *gain, float eps,
-                    int B, int R, int row0, int d_model, void *out, hipStream_t st) {
-    int rows = B * (R - row0);
+void launch_rmsnorm(int dtype, float *x, const float *part, int S, const void *gain, float eps, int B, int R, int row0,
+                    int d_model, void *out, hipStream_t st) {
+    int rows = B * (R - row0), M_all = B * R;
+    ActLayout mt_out = act_layout(rows);
+    size_t stride = (size_t)M_all * d_model;
     if (dtype == TIDAR_BF16)
-        rmsnorm_kernel<bf16_t><<<rows, 256, 0, st>>>(x, part, S, part_stride, (const bf16_t *)gain, eps, R, row0,
-                                                      d_model, (bf16_t *)out);
+        rmsnorm_kernel<bf16_t><<<rows, 256, 0, st>>>(x, part, S, stride, (const bf16_t *)gain, eps, R, row0, d_model,
+                                                      M_all, (bf16_t *)out, mt_out);
     else
-        rmsnorm_kernel<float><<<rows, 256, 0, st>>>(x, part, S, part_stride, (const float *)gain, eps, R, row0,
-                                                     d_model, (float *)out);
+        rmsnorm_kernel<float><<<rows, 256, 0, st>>>(x, part, S, stride, (const float *)gain, eps, R, row0, d_model,
+                                                     M_all, (float *)out, mt_out);
 }
 
-void launch_gemm_f32(const float *a, const float *w, float *out, int M, int N, int K, hipStream_t st) {
+void launch_gemm_f32(const float *a, const float *w, float *out, int M, int N, int K, int out_row_major,
+                     hipStream_t st) {
     dim3 grid((N + 63) / 64, (M + 15) / 16);
-    gemm_f32_kernel<<<grid, 256, 0, st>>>(a, w, out, M, N, K);
+    gemm_f32_kernel<<<grid, 256, 0, st>>>(a, w, out, M, N, K, out_row_major);
 }
 
-void launch_rope_kv(int dtype, const float *qkv_part, int S, size_t part_stride, const float *rope_cs,
-                    const int32_t *prefix_len, RowDesc d, int B, int n_q, KvView kv, void *q_out, void *k_scr,
-                    void *v_scr, hipStream_t st) {
-    int rows = B * d.R;
+void launch_pack_act(int dtype, const void *src, int M, int K, void *dst, hipStream_t st) {
+    size_t n = (size_t)M * (K / 8);
+    ActLayout mt = act_layout(M);
     if (dtype == TIDAR_BF16)
-        rope_kv_kernel<bf16_t><<<rows, 256, 0, st>>>(qkv_part, S, part_stride, rope_cs, prefix_len, d, n_q, kv,
+        pack_act_kernel<bf16_t><<<grid_for(n, 256, 8192), 256, 0, st>>>((const bf16_t *)src, M, K, (bf16_t *)dst, mt);
+    else
+        pack_act_kernel<float><<<grid_for(n, 256, 8192), 256, 0, st>>>((const float *)src, M, K, (float *)dst, mt);
+}
+
+void launch_untile_sum(const float *part, int S, int M, int N, float *out, hipStream_t st) {
+    untile_sum_kernel<<<grid_for((size_t)M * N, 256, 8192), 256, 0, st>>>(part, S, M, N, out);
+}
+
+void launch_rope_kv(int dtype, const float *qkv_part, int S, const float *rope_cs, const int32_t *prefix_len, RowDesc d,
+                    int B, int n_q, KvView kv, void *q_out, void *k_scr, void *v_scr, hipStream_t st) {
+    int rows = B * d.R;
+    size_t stride = (size_t)rows * (n_q + 2 * kv.n_kv) * kv.hd;
+    if (dtype == TIDAR_BF16)
+        rope_kv_kernel<bf16_t><<<rows, 256, 0, st>>>(qkv_part, S, stride, rope_cs, prefix_len, d, n_q, rows, kv,
                                                       (bf16_t *)q_out, (bf16_t *)k_scr, (bf16_t *)v_scr);
     else
-        rope_kv_kernel<float><<<rows, 256, 0, st>>>(qkv_part, S, part_stride, rope_cs, prefix_len, d, n_q, kv,
+        rope_kv_kernel<float><<<rows, 256, 0, st>>>(qkv_part, S, stride, rope_cs, prefix_len, d, n_q, rows, kv,
                                                      (float *)q_out, (float *)k_scr, (float *)v_scr);
 }
 
@@ -529,18 +610,21 @@ void launch_place_kv(int dtype, const void *k_new, const void *v_new, const int3
 }
 
 void launch_attention_f32(const float *q, KvView kv, const float *k_scr, const float *v_scr,
-                          const int32_t *prefix_len, RowDesc d, int B, int n_q, float *out, hipStream_t st) {
+                          const int32_t *prefix_len, RowDesc d, int B, int n_q, float *out, int out_af,
+                          hipStream_t st) {
     dim3 grid(B * d.R, n_q);
-    attention_f32_kernel<<<grid, 64, 0, st>>>(q, kv, k_scr, v_scr, prefix_len, d, n_q, out);
+    attention_f32_kernel<<<grid, 64, 0, st>>>(q, kv, k_scr, v_scr, prefix_len, d, n_q, out, out_af,
+                                              act_layout(B * d.R));
 }
 
-void launch_swiglu(int dtype, const float *part, int S, size_t part_stride, int M, int d_ff, void *out,
-                   hipStream_t st) {
-    size_t n = (size_t)M * d_ff;
+void launch_swiglu(int dtype, const float *part, int S, int M, int d_ff, void *out, hipStream_t st) {
+    size_t n = (size_t)M * (d_ff / 4);
+    size_t stride = (size_t)M * 2 * d_ff;
+    ActLayout mt = act_layout(M);
     if (dtype == TIDAR_BF16)
-        swiglu_kernel<bf16_t><<<grid_for(n, 256, 8192), 256, 0, st>>>(part, S, part_stride, M, d_ff, (bf16_t *)out);
+        swiglu_kernel<bf16_t><<<grid_for(n, 256, 8192), 256, 0, st>>>(part, S, stride, M, d_ff, (bf16_t *)out, mt);
     else
-        swiglu_kernel<float><<<grid_for(n, 256, 8192), 256, 0, st>>>(part, S, part_stride, M, d_ff, (float *)out);
+        swiglu_kernel<float><<<grid_for(n, 256, 8192), 256, 0, st>>>(part, S, stride, M, d_ff, (float *)out, mt);
 }
 
 void launch_argmax_rows(const float *logits, int B, int Rh, int vocab, int n_choose, const int32_t *pos_rows,
@@ -567,8 +651,4 @@ void launch_finish_prefill(const int32_t *y, int k, int seq, int add_len, int la
 
 void launch_set_i32(int32_t *p, int n, int32_t v, hipStream_t st) {
     set_i32_kernel<<<(n + 255) / 256, 256, 0, st>>>(p, n, v);
-}
-
-void launch_sum_partials(const float *part, int S, size_t stride, float *out, hipStream_t st) {
-    sum_partials_kernel<<<grid_for(stride, 256, 8192), 256, 0, st>>>(part, S, stride, out);
 }

@@ -9,6 +9,7 @@
 typedef __bf16 bf16_t;
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 // Row structure of one forward, identical for every sequence of the batch.
 // Rows per sequence: nc causal rows, then nb blocks of bl mask rows.
@@ -40,6 +41,32 @@ __host__ __device__ inline RowInfo row_info(const RowDesc &d, int r, int L) {
         ri.blk = j;
     }
     return ri;
+}
+
+// Activation layout of every GEMM input: the register image of the MFMA A operand, so that the slice a
+// workgroup stages for a chunk of K is one contiguous block.  Two forms, chosen by the row count M:
+//   M <= 32 ("narrow", 16x16x32 MFMA): [k step of 32][16-row tile][lane][8], lane = (k/8 % 4) * 16 + row % 16
+//   M  > 32 ("wide",   32x32x16 MFMA): [k step of 16][32-row tile][lane][8], lane = (k/8 % 2) * 32 + row % 32
+// Rows are padded to the tile height; pad rows are never written and results are never stored from them.
+struct ActLayout {
+    int wide;    // 0: narrow, 1: wide
+    int tiles;   // row tiles
+};
+__host__ __device__ inline ActLayout act_layout(int M) {
+    ActLayout a;
+    a.wide = M > 32;
+    a.tiles = a.wide ? (M + 31) / 32 : (M + 15) / 16;
+    return a;
+}
+__host__ __device__ inline size_t af_index(int row, int k, ActLayout a) {
+    if (a.wide)
+        return ((((size_t)(k >> 4) * a.tiles + (row >> 5)) * 64) + ((k >> 3) & 1) * 32 + (row & 31)) * 8 + (k & 7);
+    return ((((size_t)(k >> 5) * a.tiles + (row >> 4)) * 64) + ((k >> 3) & 3) * 16 + (row & 15)) * 8 + (k & 7);
+}
+__host__ __device__ inline size_t af_elems(int rows, int K) { return (size_t)((rows + 31) / 32) * 32 * K; }
+// Layout of every GEMM output except the logits: [split][16-column tile][row][16] fp32.
+__host__ __device__ inline size_t pt_index(int n, int row, int M) {
+    return ((size_t)(n >> 4) * M + row) * 16 + (n & 15);
 }
 
 // Paged cache geometry of one layer.
@@ -75,22 +102,27 @@ struct GemmPlan {
 GemmPlan plan_gemm_bf16(int M, int N, int K, bool force_single_split);
 
 // ---- launchers (each enqueues on `st`, checks nothing: callers validated shapes) ----
-void launch_pack_weight(int dtype, const void *src, int rows, int cols, void *dst, int tile_off, int tile_stride,
-                        hipStream_t st);
+void launch_pack_weight(int dtype, const void *src, int rows, int cols, void *dst, int dst_rows, int tile_off,
+                        int tile_stride, hipStream_t st);
 
 void launch_embed_rows(int dtype, const void *embed, const int32_t *tokens, int tok_stride, const int32_t *prefix_len,
                        RowDesc d, int B, int d_model, int mask_id, int hd, float rope_base,
                        float *x, int32_t *pos_out, float *rope_cs, hipStream_t st);
 
-// x[row] += sum_s part[s][row]; out[row'] = rmsnorm(x[row]) * gain, rows [row0, R) of each sequence.
-void launch_rmsnorm(int dtype, float *x, const float *part, int S, size_t part_stride, const void *gain, float eps,
+// x[row] += sum_s part[s][row]; out[row'] = rmsnorm(x[row]) * gain for rows [row0, R) of each sequence.
+// part is in the tiled GEMM output layout over all B*R rows, out in the A-fragment layout over B*(R-row0) rows.
+void launch_rmsnorm(int dtype, float *x, const float *part, int S, const void *gain, float eps,
                     int B, int R, int row0, int d_model, void *out, hipStream_t st);
 
 void launch_gemm_bf16(const bf16_t *a, const bf16_t *w_packed, float *out, int M, int N, int K, const GemmPlan &p,
-                      hipStream_t st);
-void launch_gemm_f32(const float *a, const float *w, float *out, int M, int N, int K, hipStream_t st);
+                      int out_row_major, hipStream_t st);
+void launch_gemm_f32(const float *a, const float *w, float *out, int M, int N, int K, int out_row_major,
+                     hipStream_t st);
+// plain row-major [M][K] -> A-fragment layout, and tiled partial sums -> plain row-major [M][N]
+void launch_pack_act(int dtype, const void *src, int M, int K, void *dst, hipStream_t st);
+void launch_untile_sum(const float *part, int S, int M, int N, float *out, hipStream_t st);
 
-void launch_rope_kv(int dtype, const float *qkv_part, int S, size_t part_stride, const float *rope_cs,
+void launch_rope_kv(int dtype, const float *qkv_part, int S, const float *rope_cs,
                     const int32_t *prefix_len, RowDesc d, int B, int n_q, KvView kv,
                     void *q_out, void *k_scr, void *v_scr, hipStream_t st);
 
@@ -109,11 +141,12 @@ void launch_attention_bf16(const bf16_t *q, KvView kv, const bf16_t *k_scr, cons
                            const int32_t *prefix_len, RowDesc d, int B, int n_q, const AttnPlan &p, float *part,
                            hipStream_t st);
 void launch_attention_combine(const float *part, int B, int R, int n_q, int n_kv, int hd, int splits, bf16_t *out,
-                              hipStream_t st);
+                              int out_af, hipStream_t st);
 void launch_attention_f32(const float *q, KvView kv, const float *k_scr, const float *v_scr,
-                          const int32_t *prefix_len, RowDesc d, int B, int n_q, float *out, hipStream_t st);
+                          const int32_t *prefix_len, RowDesc d, int B, int n_q, float *out, int out_af,
+                          hipStream_t st);
 
-void launch_swiglu(int dtype, const float *part, int S, size_t part_stride, int M, int d_ff, void *out, hipStream_t st);
+void launch_swiglu(int dtype, const float *part, int S, int M, int d_ff, void *out, hipStream_t st);
 
 // y[row] = argmax over vocab of (logits or, for the first n_choose rows of each sequence, the sampled /
 // beta-mixed value).  Rows per sequence Rh; causal row i mixes with row mix_base + i*mix_stride when beta != 1.
@@ -127,4 +160,3 @@ void launch_finish_ar(const int32_t *y, int B, int32_t *prefix_len, int32_t *tok
 void launch_finish_prefill(const int32_t *y, int k, int seq, int add_len, int last, int32_t *prefix_len,
                            int32_t *first_drafts, hipStream_t st);
 void launch_set_i32(int32_t *p, int n, int32_t v, hipStream_t st);
-void launch_sum_partials(const float *part, int S, size_t stride, float *out, hipStream_t st);

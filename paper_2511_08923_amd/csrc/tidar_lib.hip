@@ -90,7 +90,7 @@ Layout make_layout(const tidar_config &c, int B, int R, int n_mask, int Mh, int 
     l.pos = take((size_t)M * 4);
     l.rope_cs = take((size_t)M * c.head_dim * 4);
     l.x = take((size_t)M * c.d_model * 4);
-    l.xn = take((size_t)M * c.d_model * es);
+    l.xn = take(af_elems(M, c.d_model) * es);
     size_t g = gemm_out_floats(c, M, q_dim + 2 * kv_dim, c.d_model);
     size_t g2 = gemm_out_floats(c, M, c.d_model, q_dim);
     size_t g3 = gemm_out_floats(c, M, 2 * c.d_ff, c.d_model);
@@ -111,9 +111,9 @@ Layout make_layout(const tidar_config &c, int B, int R, int n_mask, int Mh, int 
         pf = attn_partial_floats(B, c.n_kv_heads, c.n_q_heads / c.n_kv_heads, R, c.head_dim, ap.splits);
     }
     l.attn_part = take(pf * 4);
-    l.o = take((size_t)M * q_dim * es);
-    l.h = take((size_t)M * c.d_ff * es);
-    l.xh = take((size_t)(Mh > 0 ? Mh : 1) * c.d_model * es);
+    l.o = take(af_elems(M, q_dim) * es);
+    l.h = take(af_elems(M, c.d_ff) * es);
+    l.xh = take(af_elems(Mh > 0 ? Mh : 1, c.d_model) * es);
     l.logits = take(own_logits ? (size_t)(Mh > 0 ? Mh : 1) * c.vocab * 4 : 0);
     l.y = take((size_t)(Mh > 0 ? Mh : 1) * 4);
     l.total = off;
@@ -138,6 +138,8 @@ bool shape_ok(const tidar_config &c) {
         return false;
     }
     if (!(c.rope_base > 1.f) || !(c.rms_eps >= 0.f)) return false;
+    if ((int64_t)c.vocab * c.d_model * 2 > 0x7fff0000ll || (int64_t)c.d_ff * c.d_model * 4 > 0x7fff0000ll)
+        return false;                          // buffer-load offsets are 32-bit
     return true;
 }
 
@@ -170,16 +172,17 @@ KvView layer_view(const tidar_config &c, const tidar_kv_cache *kv, int layer) {
     return v;
 }
 
-void gemm(tidar_ctx *ctx, const void *a, const void *w, float *out, int M, int N, int K, bool single, int *S,
+// `head` selects the LM-head form: one split, plain row-major output (the logits the caller may ask for)
+void gemm(tidar_ctx *ctx, const void *a, const void *w, float *out, int M, int N, int K, bool head, int *S,
           hipStream_t st) {
     Prof p(ctx, KC_GEMM, st);
     if (ctx->cfg.dtype == TIDAR_BF16) {
-        GemmPlan gp = plan_gemm_bf16(M, N, K, single);
+        GemmPlan gp = plan_gemm_bf16(M, N, K, head);
         *S = gp.splits;
-        launch_gemm_bf16((const bf16_t *)a, (const bf16_t *)w, out, M, N, K, gp, st);
+        launch_gemm_bf16((const bf16_t *)a, (const bf16_t *)w, out, M, N, K, gp, head ? 1 : 0, st);
     } else {
         *S = 1;
-        launch_gemm_f32((const float *)a, (const float *)w, out, M, N, K, st);
+        launch_gemm_f32((const float *)a, (const float *)w, out, M, N, K, head ? 1 : 0, st);
     }
 }
 
@@ -197,12 +200,12 @@ void attention(tidar_ctx *ctx, const Layout &l, char *ws, KvView kvv, const int3
         {
             Prof p(ctx, KC_ATTN_COMBINE, st);
             launch_attention_combine((const float *)(ws + l.attn_part), B, d.R, c.n_q_heads, c.n_kv_heads, c.head_dim,
-                                     ap.splits, (bf16_t *)o_out, st);
+                                     ap.splits, (bf16_t *)o_out, 1, st);
         }
     } else {
         Prof p(ctx, KC_ATTN, st);
         launch_attention_f32((const float *)(ws + l.q), kvv, (const float *)(ws + l.k_scr),
-                             (const float *)(ws + l.v_scr), prefix_len, d, B, c.n_q_heads, (float *)o_out, st);
+                             (const float *)(ws + l.v_scr), prefix_len, d, B, c.n_q_heads, (float *)o_out, 1, st);
     }
 }
 
@@ -228,27 +231,26 @@ void forward_rows(tidar_ctx *ctx, const tidar_weights *w, const tidar_kv_cache *
         KvView kvv = layer_view(c, kv, layer);
         {
             Prof p(ctx, KC_RMSNORM, st);
-            launch_rmsnorm(c.dtype, x, gout, S_prev, (size_t)M * c.d_model, w->attn_norm[layer], c.rms_eps, B, d.R, 0,
-                           c.d_model, ws + l.xn, st);
+            launch_rmsnorm(c.dtype, x, gout, S_prev, w->attn_norm[layer], c.rms_eps, B, d.R, 0, c.d_model, ws + l.xn,
+                           st);
         }
         int S = 1;
         gemm(ctx, ws + l.xn, w->wqkv[layer], gout, M, q_dim + 2 * kv_dim, c.d_model, false, &S, st);
         {
             Prof p(ctx, KC_ROPE_KV, st);
-            launch_rope_kv(c.dtype, gout, S, (size_t)M * (q_dim + 2 * kv_dim), (const float *)(ws + l.rope_cs),
-                           prefix_len, d, B, c.n_q_heads, kvv, ws + l.q, ws + l.k_scr, ws + l.v_scr, st);
+            launch_rope_kv(c.dtype, gout, S, (const float *)(ws + l.rope_cs), prefix_len, d, B, c.n_q_heads, kvv,
+                           ws + l.q, ws + l.k_scr, ws + l.v_scr, st);
         }
         attention(ctx, l, ws, kvv, prefix_len, d, B, max_keys, ws + l.o, st);
         gemm(ctx, ws + l.o, w->wo[layer], gout, M, c.d_model, q_dim, false, &S, st);
         {
             Prof p(ctx, KC_RMSNORM, st);
-            launch_rmsnorm(c.dtype, x, gout, S, (size_t)M * c.d_model, w->ffn_norm[layer], c.rms_eps, B, d.R, 0,
-                           c.d_model, ws + l.xn, st);
+            launch_rmsnorm(c.dtype, x, gout, S, w->ffn_norm[layer], c.rms_eps, B, d.R, 0, c.d_model, ws + l.xn, st);
         }
         gemm(ctx, ws + l.xn, w->w_gate_up[layer], gout, M, 2 * c.d_ff, c.d_model, false, &S, st);
         {
             Prof p(ctx, KC_SWIGLU, st);
-            launch_swiglu(c.dtype, gout, S, (size_t)M * 2 * c.d_ff, M, c.d_ff, ws + l.h, st);
+            launch_swiglu(c.dtype, gout, S, M, c.d_ff, ws + l.h, st);
         }
         gemm(ctx, ws + l.h, w->w_down[layer], gout, M, c.d_model, c.d_ff, false, &S, st);
         S_prev = S;
@@ -258,8 +260,7 @@ void forward_rows(tidar_ctx *ctx, const tidar_weights *w, const tidar_kv_cache *
     const int Mh = B * Rh;
     {
         Prof p(ctx, KC_RMSNORM, st);
-        launch_rmsnorm(c.dtype, x, gout, S_prev, (size_t)M * c.d_model, w->final_norm, c.rms_eps, B, d.R, head_row0,
-                       c.d_model, ws + l.xh, st);
+        launch_rmsnorm(c.dtype, x, gout, S_prev, w->final_norm, c.rms_eps, B, d.R, head_row0, c.d_model, ws + l.xh, st);
     }
     float *logits = logits_dst ? logits_dst : (float *)(ws + l.logits);
     int S = 1;
@@ -355,7 +356,7 @@ void tidar_destroy(tidar_ctx *ctx) {
 
 size_t tidar_packed_weight_bytes(int32_t dtype, int32_t rows, int32_t cols) {
     if (rows <= 0 || cols <= 0) return 0;
-    return (size_t)rows * cols * esize(dtype);
+    return (size_t)((rows + 31) / 32) * 32 * cols * esize(dtype);      // rows padded to the 32-row tile
 }
 
 tidar_status tidar_pack_weight(int32_t dtype, const void *src, int32_t rows, int32_t cols, void *dst,
@@ -366,7 +367,7 @@ tidar_status tidar_pack_weight(int32_t dtype, const void *src, int32_t rows, int
     if (dtype == TIDAR_BF16 && cols % 32) return TIDAR_EINVAL;
     int last_tile = dst_tile_offset + (rows / 16 - 1) * dst_tile_stride;
     if (last_tile >= dst_rows / 16) return TIDAR_EINVAL;
-    launch_pack_weight(dtype, src, rows, cols, dst, dst_tile_offset, dst_tile_stride, (hipStream_t)stream);
+    launch_pack_weight(dtype, src, rows, cols, dst, dst_rows, dst_tile_offset, dst_tile_stride, (hipStream_t)stream);
     return TIDAR_OK;
 }
 
@@ -534,44 +535,35 @@ tidar_status tidar_hybrid_attention(tidar_ctx *ctx, const tidar_kv_cache *kv, in
         }
         Prof p(ctx, KC_ATTN_COMBINE, st);
         launch_attention_combine((const float *)(wsb + 2 * scr), batch, d.R, c.n_q_heads, c.n_kv_heads, c.head_dim,
-                                 ap.splits, (bf16_t *)out, st);
+                                 ap.splits, (bf16_t *)out, 0, st);
     } else {
         Prof p(ctx, KC_ATTN, st);
         launch_attention_f32((const float *)q, kvv, (const float *)wsb, (const float *)(wsb + scr), prefix_len, d,
-                             batch, c.n_q_heads, (float *)out, st);
+                             batch, c.n_q_heads, (float *)out, 0, st);
     }
     return TIDAR_OK;
 }
 
 size_t tidar_gemm_workspace_bytes(int32_t dtype, int32_t M, int32_t N, int32_t K) {
-    if (dtype != TIDAR_BF16 || M < 1 || N < 16 || K < 32) return 256;
-    GemmPlan p = plan_gemm_bf16(M, N, K, false);
-    return p.splits > 1 ? align_up((size_t)p.splits * M * N * 4) : 256;
+    if (M < 1 || N < 16 || K < 8) return 256;
+    int splits = dtype == TIDAR_BF16 ? plan_gemm_bf16(M, N, K, false).splits : 1;
+    return align_up(af_elems(M, K) * esize(dtype)) + align_up((size_t)splits * M * N * 4);
 }
 
 tidar_status tidar_gemm(tidar_ctx *ctx, const void *a, const void *w_packed, float *out, int32_t M, int32_t N,
                         int32_t K, void *ws, size_t ws_bytes, void *stream) {
-    if (!ctx || !a || !w_packed || !out || M < 1 || N < 1 || K < 1) return TIDAR_EINVAL;
-    if (N % 16) return TIDAR_EINVAL;
+    if (!ctx || !a || !w_packed || !out || !ws || M < 1 || N < 1 || K < 1) return TIDAR_EINVAL;
+    if (N % 16 || K % 8) return TIDAR_EINVAL;
+    const int dtype = ctx->cfg.dtype;
+    if (dtype == TIDAR_BF16 && K % 32) return TIDAR_EINVAL;
+    if (ws_bytes < tidar_gemm_workspace_bytes(dtype, M, N, K)) return TIDAR_ENOMEM;
     hipStream_t st = (hipStream_t)stream;
-    if (ctx->cfg.dtype == TIDAR_BF16) {
-        if (K % 32) return TIDAR_EINVAL;
-        GemmPlan p = plan_gemm_bf16(M, N, K, false);
-        if (p.splits > 1) {
-            if (!ws || ws_bytes < (size_t)p.splits * M * N * 4) return TIDAR_ENOMEM;
-            {
-                Prof pr(ctx, KC_GEMM, st);
-                launch_gemm_bf16((const bf16_t *)a, (const bf16_t *)w_packed, (float *)ws, M, N, K, p, st);
-            }
-            launch_sum_partials((const float *)ws, p.splits, (size_t)M * N, out, st);
-        } else {
-            Prof pr(ctx, KC_GEMM, st);
-            launch_gemm_bf16((const bf16_t *)a, (const bf16_t *)w_packed, out, M, N, K, p, st);
-        }
-    } else {
-        Prof pr(ctx, KC_GEMM, st);
-        launch_gemm_f32((const float *)a, (const float *)w_packed, out, M, N, K, st);
-    }
+    char *a_frag = (char *)ws;
+    float *part = (float *)((char *)ws + align_up(af_elems(M, K) * esize(dtype)));
+    launch_pack_act(dtype, a, M, K, a_frag, st);       // the step's producers write this layout directly
+    int S = 1;
+    gemm(ctx, a_frag, w_packed, part, M, N, K, false, &S, st);
+    launch_untile_sum(part, S, M, N, out, st);
     return TIDAR_OK;
 }
 

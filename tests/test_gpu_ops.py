@@ -28,7 +28,7 @@ def _gemm(T, ctx, a, w):
     M, K = a.shape
     N = w.shape[0]
     ad, wd = a.cuda(), w.cuda()
-    packed = torch.empty(N * K, dtype=torch.bfloat16, device="cuda")
+    packed = torch.zeros(T.tidar_packed_weight_bytes(T.TIDAR_BF16, N, K) // 2, dtype=torch.bfloat16, device="cuda")
     T.tidar_pack_weight(T.TIDAR_BF16, wd, packed, N)
     out = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
     ws = torch.empty(T.tidar_gemm_workspace_bytes(T.TIDAR_BF16, M, N, K), dtype=torch.uint8, device="cuda")
