@@ -137,7 +137,7 @@ struct AttnPlan {
 AttnPlan plan_attention(int B, int n_kv, int group, int R, int max_keys);
 size_t attn_partial_floats(int B, int n_kv, int group, int R, int hd, int splits);
 
-void launch_attention_bf16(const bf16_t *q, KvView kv, const bf16_t *k_scr, const bf16_t *v_scr,
+void launch_attention_bf16(const bf16_t *q, KvView kv, int n_pages, const bf16_t *k_scr, const bf16_t *v_scr,
                            const int32_t *prefix_len, RowDesc d, int B, int n_q, const AttnPlan &p, float *part,
                            hipStream_t st);
 void launch_attention_combine(const float *part, int B, int R, int n_q, int n_kv, int hd, int splits, bf16_t *out,

@@ -186,14 +186,14 @@ void gemm(tidar_ctx *ctx, const void *a, const void *w, float *out, int M, int N
     }
 }
 
-void attention(tidar_ctx *ctx, const Layout &l, char *ws, KvView kvv, const int32_t *prefix_len, RowDesc d, int B,
-               int max_keys, void *o_out, hipStream_t st) {
+void attention(tidar_ctx *ctx, const Layout &l, char *ws, KvView kvv, int n_pages, const int32_t *prefix_len,
+               RowDesc d, int B, int max_keys, void *o_out, hipStream_t st) {
     const tidar_config &c = ctx->cfg;
     if (c.dtype == TIDAR_BF16) {
         AttnPlan ap = plan_attention(B, c.n_kv_heads, c.n_q_heads / c.n_kv_heads, d.R, max_keys);
         {
             Prof p(ctx, KC_ATTN, st);
-            launch_attention_bf16((const bf16_t *)(ws + l.q), kvv, (const bf16_t *)(ws + l.k_scr),
+            launch_attention_bf16((const bf16_t *)(ws + l.q), kvv, n_pages, (const bf16_t *)(ws + l.k_scr),
                                   (const bf16_t *)(ws + l.v_scr), prefix_len, d, B, c.n_q_heads, ap,
                                   (float *)(ws + l.attn_part), st);
         }
@@ -241,7 +241,7 @@ void forward_rows(tidar_ctx *ctx, const tidar_weights *w, const tidar_kv_cache *
             launch_rope_kv(c.dtype, gout, S, (const float *)(ws + l.rope_cs), prefix_len, d, B, c.n_q_heads, kvv,
                            ws + l.q, ws + l.k_scr, ws + l.v_scr, st);
         }
-        attention(ctx, l, ws, kvv, prefix_len, d, B, max_keys, ws + l.o, st);
+        attention(ctx, l, ws, kvv, kv->n_pages, prefix_len, d, B, max_keys, ws + l.o, st);
         gemm(ctx, ws + l.o, w->wo[layer], gout, M, c.d_model, q_dim, false, &S, st);
         {
             Prof p(ctx, KC_RMSNORM, st);
@@ -530,8 +530,9 @@ tidar_status tidar_hybrid_attention(tidar_ctx *ctx, const tidar_kv_cache *kv, in
     if (c.dtype == TIDAR_BF16) {
         {
             Prof p(ctx, KC_ATTN, st);
-            launch_attention_bf16((const bf16_t *)q, kvv, (const bf16_t *)wsb, (const bf16_t *)(wsb + scr), prefix_len,
-                                  d, batch, c.n_q_heads, ap, (float *)(wsb + 2 * scr), st);
+            launch_attention_bf16((const bf16_t *)q, kvv, kv->n_pages, (const bf16_t *)wsb,
+                                  (const bf16_t *)(wsb + scr), prefix_len, d, batch, c.n_q_heads, ap,
+                                  (float *)(wsb + 2 * scr), st);
         }
         Prof p(ctx, KC_ATTN_COMBINE, st);
         launch_attention_combine((const float *)(wsb + 2 * scr), batch, d.R, c.n_q_heads, c.n_kv_heads, c.head_dim,
