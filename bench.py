@@ -43,6 +43,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch every kernel from the host instead of replaying "
                     "a captured HIP graph of the step")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain device copy of 1 GiB ten times (known traffic: 1 GiB read + 1 GiB written "
+                         "per launch) so that rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings can be scaled")
     ap.add_argument("--traffic-kib", type=str, default=None,
                     help="FETCH_SIZE,WRITE_SIZE per gemm launch (KiB, already scaled) measured with rocprofv3 --pmc")
     return ap.parse_args()
@@ -92,6 +95,14 @@ def main():
 
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        src = torch.zeros(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": {"bytes_read": 1 << 30, "bytes_written": 1 << 30, "launches": 10}}))
+        return
     shape = TI.SHAPES[args.shape]
     if args.layers != shape.n_layers:
         shape = shape.with_layers(args.layers)
