@@ -152,7 +152,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_small_kernel(const bf16_t *__re
 template <int MTA>
 __global__ __launch_bounds__(256) void gemm_bf16_large_kernel(const bf16_t *__restrict__ a,
                                                               const bf16_t *__restrict__ w, float *__restrict__ out,
-                                                              int M, int N, int K, int splits, int out_row_major) {
+                                                              int M, int N, int K, int splits, int epi) {
     constexpr int NT = 2, KS = 8, PFK = 16;
     constexpr int CTL = (MTA == 5) ? 9 : 2 * MTA;
     constexpr int PIECES = CTL * KS * 64;        // 16-byte pieces per chunk
@@ -258,22 +258,55 @@ __global__ __launch_bounds__(256) void gemm_bf16_large_kernel(const bf16_t *__re
         }
     }
 
-    // ---- epilogue: D lane l register i = row 8*(i/4) + 4*(l/32) + i%4, column l%32
+    // ---- epilogue.  D lane l register e = row 8*(e/4) + 4*(l/32) + e%4, column l%32: a lane owns one column, so
+    // each 32x32 tile is turned through a private LDS patch (the staging buffers are free after the last
+    // barrier) and leaves as 16-byte pieces: 4 wide stores per tile instead of 16 narrow ones.
+    const int lq = lane & 31, lh = lane >> 5;
+    if (epi == GEMM_EPI_SWIGLU) {
+        // columns 0-15 of a tile are gate, 16-31 up, of the same 16 features (tile T = features 16T..16T+15 =
+        // exactly one k step of the next GEMM's A-fragment layout): h = silu(gate) * up, stored as one fragment
+        bf16_t *hs = reinterpret_cast<bf16_t *>(gemm_smem) + wave * (32 * 16);
+        bf16_t *ho = reinterpret_cast<bf16_t *>(out);
+#pragma unroll
+        for (int mt = 0; mt < MTA; ++mt) {
+            const int tile_r = mh * MTA + mt;
+#pragma unroll
+            for (int j = 0; j < NT; ++j) {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const float v = acc[mt][j][e];
+                    const float u = __shfl_xor(v, 16);
+                    if (lq < 16)
+                        hs[(8 * (e >> 2) + 4 * lh + (e & 3)) * 16 + lq] = (bf16_t)(v / (1.f + __expf(-v)) * u);
+                }
+                const bf16x8 piece = *(const bf16x8 *)(hs + lq * 16 + 8 * lh);
+                if (tile_r < ct_here && tile0 + j < t32)
+                    *(bf16x8 *)(ho + (((size_t)(tile0 + j) * m_tiles + mt_base + tile_r) * 64 + lane) * 8) = piece;
+            }
+        }
+        return;
+    }
+    float *scr = reinterpret_cast<float *>(gemm_smem) + wave * (32 * 36);
     float *o = out + (size_t)blockIdx.y * M * N;
 #pragma unroll
     for (int mt = 0; mt < MTA; ++mt) {
         const int tile_r = mh * MTA + mt;
-        if (tile_r >= ct_here) continue;          // also drops the repeated tile
+        if (tile_r >= ct_here) continue;          // also drops the repeated tile (wave-uniform)
 #pragma unroll
         for (int j = 0; j < NT; ++j) {
-            const int col = (tile0 + j) * 32 + (lane & 31);
-            if (col >= N) continue;
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int row = (mt_base + tile_r) * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-                if (row < M) {
-                    size_t idx = out_row_major ? (size_t)row * N + col : ((size_t)(col >> 4) * M + row) * 16 + (col & 15);
-                    o[idx] = acc[mt][j][e];
+            for (int e = 0; e < 16; ++e) scr[(8 * (e >> 2) + 4 * lh + (e & 3)) * 36 + lq] = acc[mt][j][e];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int idx = lane + 64 * i;
+                const int r = idx >> 3, c4 = idx & 7;
+                const f32x4 v = *(const f32x4 *)(scr + r * 36 + 4 * c4);
+                const int row = (mt_base + tile_r) * 32 + r;
+                const int col = (tile0 + j) * 32 + 4 * c4;
+                if (row < M && col < N) {
+                    const size_t oi = (epi == GEMM_EPI_ROWMAJOR) ? (size_t)row * N + col
+                                                                 : ((size_t)(col >> 4) * M + row) * 16 + (col & 15);
+                    *(f32x4 *)(o + oi) = v;
                 }
             }
         }
@@ -288,7 +321,7 @@ void launch_small(const bf16_t *a, const bf16_t *w, float *out, int M, int N, in
 }
 
 template <int MTA>
-void launch_large(const bf16_t *a, const bf16_t *w, float *out, int M, int N, int K, const GemmPlan &p, int row_major,
+void launch_large(const bf16_t *a, const bf16_t *w, float *out, int M, int N, int K, const GemmPlan &p, int epi,
                   hipStream_t st) {
     constexpr int CTL = (MTA == 5) ? 9 : 2 * MTA;
     int m_tiles = (M + 31) / 32;
@@ -300,7 +333,7 @@ void launch_large(const bf16_t *a, const bf16_t *w, float *out, int M, int N, in
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)SMEM);
         attr_set = true;
     }
-    gemm_bf16_large_kernel<MTA><<<grid, 256, SMEM, st>>>(a, w, out, M, N, K, p.splits, row_major);
+    gemm_bf16_large_kernel<MTA><<<grid, 256, SMEM, st>>>(a, w, out, M, N, K, p.splits, epi);
 }
 
 }  // namespace

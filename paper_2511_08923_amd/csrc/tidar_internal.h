@@ -114,8 +114,12 @@ void launch_embed_rows(int dtype, const void *embed, const int32_t *tokens, int 
 void launch_rmsnorm(int dtype, float *x, const float *part, int S, const void *gain, float eps,
                     int B, int R, int row0, int d_model, void *out, hipStream_t st);
 
+// Epilogue forms of the bf16 GEMM: tiled fp32 partial sums (default), plain row-major fp32 (the logits), or, for the
+// interleaved gate/up matrix with one split and M > 32, SwiGLU applied in registers and h written as bf16 straight
+// into the A-fragment layout of the down projection (out is then a bf16 buffer of af_elems(M, N/2)).
+enum { GEMM_EPI_TILED = 0, GEMM_EPI_ROWMAJOR = 1, GEMM_EPI_SWIGLU = 2 };
 void launch_gemm_bf16(const bf16_t *a, const bf16_t *w_packed, float *out, int M, int N, int K, const GemmPlan &p,
-                      int out_row_major, hipStream_t st);
+                      int epi, hipStream_t st);
 void launch_gemm_f32(const float *a, const float *w, float *out, int M, int N, int K, int out_row_major,
                      hipStream_t st);
 // plain row-major [M][K] -> A-fragment layout, and tiled partial sums -> plain row-major [M][N]

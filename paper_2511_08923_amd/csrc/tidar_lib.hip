@@ -179,7 +179,8 @@ void gemm(tidar_ctx *ctx, const void *a, const void *w, float *out, int M, int N
     if (ctx->cfg.dtype == TIDAR_BF16) {
         GemmPlan gp = plan_gemm_bf16(M, N, K, head);
         *S = gp.splits;
-        launch_gemm_bf16((const bf16_t *)a, (const bf16_t *)w, out, M, N, K, gp, head ? 1 : 0, st);
+        launch_gemm_bf16((const bf16_t *)a, (const bf16_t *)w, out, M, N, K, gp,
+                         head ? GEMM_EPI_ROWMAJOR : GEMM_EPI_TILED, st);
     } else {
         *S = 1;
         launch_gemm_f32((const float *)a, (const float *)w, out, M, N, K, head ? 1 : 0, st);
@@ -247,8 +248,18 @@ void forward_rows(tidar_ctx *ctx, const tidar_weights *w, const tidar_kv_cache *
             Prof p(ctx, KC_RMSNORM, st);
             launch_rmsnorm(c.dtype, x, gout, S, w->ffn_norm[layer], c.rms_eps, B, d.R, 0, c.d_model, ws + l.xn, st);
         }
-        gemm(ctx, ws + l.xn, w->w_gate_up[layer], gout, M, 2 * c.d_ff, c.d_model, false, &S, st);
-        {
+        bool fused_swiglu = false;
+        if (c.dtype == TIDAR_BF16 && M > 32) {
+            GemmPlan gp = plan_gemm_bf16(M, 2 * c.d_ff, c.d_model, false);
+            if (gp.splits == 1 && gp.m_chunks >= 1) {       // nothing to reduce: SwiGLU can live in the epilogue
+                Prof p(ctx, KC_GEMM, st);
+                launch_gemm_bf16((const bf16_t *)(ws + l.xn), (const bf16_t *)w->w_gate_up[layer],
+                                 (float *)(ws + l.h), M, 2 * c.d_ff, c.d_model, gp, GEMM_EPI_SWIGLU, st);
+                fused_swiglu = true;
+            }
+        }
+        if (!fused_swiglu) {
+            gemm(ctx, ws + l.xn, w->w_gate_up[layer], gout, M, 2 * c.d_ff, c.d_model, false, &S, st);
             Prof p(ctx, KC_SWIGLU, st);
             launch_swiglu(c.dtype, gout, S, M, c.d_ff, ws + l.h, st);
         }
