@@ -301,3 +301,119 @@ def test_8b_shape_two_layers_one_step_vs_oracle(T):
     if mis == 0:
         assert int(a[0]) == a_o and nxt[0].tolist() == nxt_o
     eng.close()
+
+
+# ----------------------------------------------------------------------------- 1.5B-shaped layers (config 3)
+def test_1p5b_shape_two_layers_prefill_and_steps_vs_oracle(T):
+    """1.5B-shaped layers (d 1536, 12 q / 2 kv heads, ffn 8960, tied embeddings, vocab 151936) on a 2-layer
+    model: chunked prefill of a 300-token prompt (two passes), then teacher-forced steps at k = 16."""
+    sh = TI.SHAPE_1P5B.with_layers(2)
+    w = TI.make_weights(sh, seed=3, dtype=torch.bfloat16)
+    eng = T.Engine(sh, w, dtype=T.TIDAR_BF16, max_k=16, max_batch=1, max_seq_len=512)
+    model = O.OracleModel(sh, w, dtype=torch.float64, bf16_faithful=True)
+    k, P = 16, 300
+    prompt = TI.make_prompt(sh, P, seed=33)
+    st = model.new_state(512)
+    print("1.5b-shape oracle prefill ...", flush=True)
+    d_o, lg_o = model.prefill(st, [int(t) for t in prompt[0]], k)
+    first, lg = eng.prefill(prompt, k, want_logits=True)
+    torch.cuda.synchronize()
+    err = float((lg[0].cpu().double() - lg_o).abs().max())
+    print(f"  prefill max logit err {err:.2e}", flush=True)
+    assert err < 3e-2      # logit std is 0.78 here (d_model 1536); see the 8B-shape test for the bf16 noise floor
+    mis, bad = near_tie_mismatches(lg[0].cpu().argmax(-1), lg_o, err)
+    assert bad == 0
+    for step in range(2):
+        load_oracle_state_into_engine(eng, st)
+        L = st.L
+        drafts = list(d_o)
+        a_o, acc_o, nxt_o, lg_o = model.tidar_step(st, drafts)
+        a, acc, nxt, lg = eng.step(torch.tensor([drafts], dtype=torch.int32, device="cuda"), k, hint=L,
+                                   want_logits=True)
+        torch.cuda.synchronize()
+        err = float((lg[0].cpu().double() - lg_o).abs().max())
+        mis, bad = near_tie_mismatches(lg[0].cpu().argmax(-1), lg_o, err)
+        print(f"  step {step}: max logit err {err:.2e}, near-tie rows {mis}", flush=True)
+        assert err < 3e-2 and bad == 0
+        if mis == 0:
+            assert int(a[0]) == a_o and nxt[0].tolist() == nxt_o and acc[0, :a_o].tolist() == acc_o
+        d_o = nxt_o
+    eng.close()
+
+
+# ----------------------------------------------------------------------------- batch sweep shapes (config 5)
+@pytest.mark.parametrize("B,k", [(4, 16), (8, 8), (32, 4)])
+def test_small_bf16_batched_steps_match_oracle(T, B, k):
+    """Several sequences per step with different prefix lengths (rows B*k*(k+1) up to 1088, i.e. several GEMM
+    passes): every sequence's step equals the oracle's step for that sequence alone."""
+    sh = TI.SMALL_GQA
+    w = TI.make_weights(sh, seed=3, dtype=torch.bfloat16)
+    eng = T.Engine(sh, w, dtype=T.TIDAR_BF16, max_k=16, max_batch=B, max_seq_len=256)
+    model = O.OracleModel(sh, w, bf16_faithful=True)
+    states, drafts_all, want = [], [], []
+    for b in range(B):
+        P = 20 + 7 * b
+        prompt = [int(t) for t in TI.make_prompt(sh, P, seed=100 + b)[0]]
+        st = model.new_state(256, seq_id=b)
+        d, _ = model.prefill(st, prompt, k)
+        load_oracle_state_into_engine(eng, st, seq=b)
+        states.append(st)
+        drafts_all.append(d)
+    hint = max(s.L for s in states)
+    for b in range(B):
+        want.append(model.tidar_step(states[b], drafts_all[b]))
+    a, acc, nxt, lg = eng.step(torch.tensor(drafts_all, dtype=torch.int32, device="cuda"), k, hint=hint,
+                               want_logits=True)
+    torch.cuda.synchronize()
+    n_mis = 0
+    for b in range(B):
+        a_o, acc_o, nxt_o, lg_o = want[b]
+        err = float((lg[b].cpu().double() - lg_o).abs().max())
+        assert err < LOGIT_TOL, (b, err)
+        mis, bad = near_tie_mismatches(lg[b].cpu().argmax(-1), lg_o, err)
+        assert bad == 0
+        n_mis += mis
+        if mis == 0:
+            assert int(a[b]) == a_o and nxt[b].tolist() == nxt_o and acc[b, :a_o].tolist() == acc_o
+            assert int(eng.prefix_len[b]) == states[b].L
+    print(f"  batched B={B} k={k}: near-tie rows {n_mis}", flush=True)
+    # batched AR step on the same engine
+    toks = nxt[:, 0].contiguous()
+    hint = max(s.L for s in states) + k
+    out, lg = eng.ar_step(toks, hint=hint, want_logits=True)
+    torch.cuda.synchronize()
+    for b in range(B):
+        st = states[b]
+        st_gpu_L = int(eng.prefix_len[b]) - 1
+        if st_gpu_L != st.L:
+            continue                     # a near-tie changed this sequence's acceptance above
+        tok_o, lg_o = model.ar_step(st, int(toks[b]))
+        # the device cache behind this step came from its own TiDAR step: compare within tolerance
+        assert float((lg[b].cpu().double() - lg_o[0]).abs().max()) < LOGIT_TOL
+    eng.close()
+
+
+def test_sampling_bf16_seeded_step_matches_oracle(T, small):
+    """Temperature-1 seeded sampling at the causal rows in bf16 (config 4's second mode) on the small model."""
+    eng, model = small
+    sh = TI.SMALL_GQA
+    k, P = 8, 60
+    prompt = TI.make_prompt(sh, P, seed=71)
+    omode = O.Mode(sample=True, temperature=1.0, seed=99)
+    gmode = T.make_mode(sample=True, temperature=1.0, seed=99)
+    st = model.new_state(256)
+    d_o, _ = model.prefill(st, [int(t) for t in prompt[0]], k, omode)
+    load_oracle_state_into_engine(eng, st)
+    a_o, acc_o, nxt_o, lg_o = model.tidar_step(st, d_o, omode)
+    a, acc, nxt, lg = eng.step(torch.tensor([d_o], dtype=torch.int32, device="cuda"), k, hint=P, mode=gmode,
+                               want_logits=True)
+    torch.cuda.synchronize()
+    err = float((lg[0].cpu().double() - lg_o).abs().max())
+    assert err < LOGIT_TOL
+    # sampled tokens: the device's Gumbel-max over its own logits; excuse only perturbed-score near ties
+    g = torch.from_numpy(O.gumbel_noise(99, 0, P + a_o, sh.vocab))
+    pert = lg_o[O.row_of_c(a_o)] + g
+    if int(nxt[0, 0]) != nxt_o[0]:
+        assert float(pert.max() - pert[int(nxt[0, 0])]) < 2 * err + 1e-5
+    else:
+        assert int(a[0]) == a_o
