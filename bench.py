@@ -43,6 +43,12 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch every kernel from the host instead of replaying "
                     "a captured HIP graph of the step")
+    ap.add_argument("--sweep", action="store_true",
+                    help="latency table instead of the headline line: TiDAR step vs 1-token AR step for batch in "
+                         "--sweep-batches and k in --sweep-ks at a synthetic cache of --prefix tokens per sequence "
+                         "(one JSON line per point on stdout)")
+    ap.add_argument("--sweep-batches", type=str, default="1,4,8,16,32")
+    ap.add_argument("--sweep-ks", type=str, default="4,8,16")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain device copy of 1 GiB ten times (known traffic: 1 GiB read + 1 GiB written "
                          "per launch) so that rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings can be scaled")
@@ -83,6 +89,85 @@ def cpu_baseline(shape, k, L, mean_accept):
             "step_s": full}
 
 
+def sweep(args, shape, torch, T, TI, dev):
+    """TiDAR-step vs AR-step latency over batch and block length (the free-slot regime and its crossover).
+    The cache is filled synthetically (N(0,1) K/V, as in the attention micro-benchmark): step latency does not
+    depend on token values, and a real prefill of batch x prefix tokens would only lengthen the set-up."""
+    batches = [int(x) for x in args.sweep_batches.split(",")]
+    ks = [int(x) for x in args.sweep_ks.split(",")]
+    P = args.prefix
+    bmax, kmax = max(batches), max(ks)
+    w = TI.make_weights(shape, seed=4, dtype=torch.bfloat16, device=dev)
+    eng = T.Engine(shape, w, dtype=T.TIDAR_BF16, max_k=kmax, max_batch=bmax, max_seq_len=P + 64 * kmax, device=dev,
+                   free_source=True)
+    del w
+    torch.cuda.empty_cache()
+    g = torch.Generator(device=dev)
+    g.manual_seed(7)
+    for l in range(shape.n_layers):                       # page by page would be the same bytes: fill whole layers
+        eng.k_pages[l].normal_(0.0, 1.0, generator=g)
+        eng.v_pages[l].normal_(0.0, 1.0, generator=g)
+    mode = T.make_mode()
+    wbytes = eng.weight_bytes_per_step()
+    kv_per_tok = 2 * shape.n_layers * shape.n_kv_heads * shape.head_dim * 2
+
+    def timed(fn, n_warm, n):
+        for _ in range(n_warm):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / n * 1e3
+
+    def graphed(body):
+        if args.no_graph:
+            return body
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            body()
+        torch.cuda.current_stream().wait_stream(side)
+        gr = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gr):
+            body()
+        return gr.replay
+
+    rows = []
+    for B in batches:
+        tok_in = TI.make_drafts(shape, 1, seed=11, batch=B).to(dev).view(B).contiguous()
+        tok_out = torch.empty(B, dtype=torch.int32, device=dev)
+
+        def ar_body():
+            eng.prefix_len[:B].fill_(P)                   # keep the prefix length fixed across timed steps
+            eng.ar_step(tok_in, hint=P, mode=mode, out=tok_out)
+
+        ar_ms = timed(graphed(ar_body), args.warmup, args.steps)
+        for k in ks:
+            R = k * (k + 1)
+            drafts = TI.make_drafts(shape, k, seed=12, batch=B).to(dev)
+            out = (torch.empty(B, dtype=torch.int32, device=dev), torch.empty(B, k, dtype=torch.int32, device=dev),
+                   torch.empty(B, k, dtype=torch.int32, device=dev))
+
+            def td_body():
+                eng.prefix_len[:B].fill_(P)
+                eng.step(drafts, k, hint=P, mode=mode, out=out)
+
+            td_ms = timed(graphed(td_body), args.warmup, args.steps)
+            flops = 2.0 * B * R * (wbytes / 2) + 4.0 * shape.n_layers * shape.n_q_heads * B * R * P * shape.head_dim
+            row = {"sweep": True, "batch": B, "k": k, "rows": B * R, "prefix_len": P, "tidar_step_ms": td_ms,
+                   "ar_step_ms": ar_ms, "tidar_over_ar_latency": td_ms / ar_ms,
+                   "tidar_step_hbm_GBs": (wbytes + B * kv_per_tok * P) / (td_ms * 1e-3) / 1e9,
+                   "ar_step_hbm_GBs": (wbytes + B * kv_per_tok * P) / (ar_ms * 1e-3) / 1e9,
+                   "tidar_step_tflops": flops / (td_ms * 1e-3) / 1e12,
+                   "tidar_step_mfma_frac": flops / (td_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                   "layers": shape.n_layers, "shape": shape.name}
+            rows.append(row)
+            print(json.dumps(row), flush=True)
+    eng.close()
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -106,6 +191,8 @@ def main():
     shape = TI.SHAPES[args.shape]
     if args.layers != shape.n_layers:
         shape = shape.with_layers(args.layers)
+    if args.sweep:
+        return sweep(args, shape, torch, T, TI, dev)
     k, P, V = args.k, args.prefix, shape.vocab
     R = k * (k + 1)
     n_timed = args.steps + args.warmup
