@@ -159,6 +159,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_large_kernel(const bf16_t *__re
     constexpr int STAGE = (PIECES + 255) / 256;
     constexpr int FR = KS * MTA;                 // A fragments a wave consumes per chunk
     constexpr int AFD = 3;                       // LDS -> register prefetch distance in fragments
+    static_assert(2 * STAGE <= FR, "one staging piece is stored after every other fragment");
     extern __shared__ __attribute__((aligned(16))) unsigned char gemm_smem[];
     bf16x8 *lds = reinterpret_cast<bf16x8 *>(gemm_smem);      // [2][KS][CTL][64]
 
@@ -183,26 +184,23 @@ __global__ __launch_bounds__(256) void gemm_bf16_large_kernel(const bf16_t *__re
         return buf_load(rw, (q < q1 && w_off[j] != OOB) ? w_off[j] + q * w_step : OOB);
     };
 
-    // A staging: piece p = tid + s*256 of the chunk -> (k step, row tile, lane)
-    int a_off[STAGE];
-#pragma unroll
-    for (int s = 0; s < STAGE; ++s) {
-        const int p = tid + s * 256;
-        const int ks = p / (CTL * 64), rem = p % (CTL * 64);
-        const int ct = rem >> 6, ln = rem & 63;
-        a_off[s] = (p < PIECES && ct < ct_here) ? ((ks * m_tiles + mt_base + ct) * 64 + ln) * 16 : OOB;
-    }
+    // A staging: piece p = tid + s*256 of the chunk = lane `lane` of fragment (wave + 4s) -> (k step, row tile).
+    // The fragment index is wave-uniform, so its address lives in scalar registers (the buffer load's scalar
+    // offset) and only lane*16, or the out-of-bounds offset for a fragment that does not exist, in a VGPR.
+    const int wv = __builtin_amdgcn_readfirstlane(wave);
     const int a_chunk_step = KS * m_tiles * 1024;
+    const int lane16 = lane * 16;
     bf16x8 stage[STAGE];
-    auto load_a = [&](int c) {
-#pragma unroll
-        for (int s = 0; s < STAGE; ++s)
-            stage[s] = buf_load(ra, (c < c1 && a_off[s] != OOB) ? a_off[s] + c * a_chunk_step : OOB);
+    auto load_a1 = [&](int s, int c) {
+        const int i = wv + 4 * s;
+        const int ks = i / CTL, ct = i % CTL;
+        const bool ok = i < CTL * KS && ct < ct_here && c < c1;
+        stage[s] = __builtin_bit_cast(
+            bf16x8, __builtin_amdgcn_raw_buffer_load_b128(ra, ok ? lane16 : OOB,
+                                                          (ks * m_tiles + mt_base + ct) * 1024 + c * a_chunk_step, 0));
     };
-    auto store_a = [&](int buf) {
-#pragma unroll
-        for (int s = 0; s < STAGE; ++s)
-            if (STAGE * 256 == PIECES || tid + s * 256 < PIECES) lds[buf * PIECES + tid + s * 256] = stage[s];
+    auto store_a1 = [&](int s, int buf) {
+        if (STAGE * 256 == PIECES || tid + s * 256 < PIECES) lds[buf * PIECES + tid + s * 256] = stage[s];
     };
 
     f32x16 acc[MTA][NT];
@@ -214,12 +212,17 @@ __global__ __launch_bounds__(256) void gemm_bf16_large_kernel(const bf16_t *__re
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
     bf16x8 wbuf[PFK][NT];
-    load_a(c0);
+#pragma unroll
+    for (int s = 0; s < STAGE; ++s) load_a1(s, c0);
 #pragma unroll
     for (int s = 0; s < PFK; ++s)
 #pragma unroll
         for (int j = 0; j < NT; ++j) wbuf[s][j] = ld_w(j, q0 + s);
-    store_a(0);
+#pragma unroll
+    for (int s = 0; s < STAGE; ++s) {
+        store_a1(s, 0);
+        load_a1(s, c0 + 1);
+    }
     __syncthreads();
 
     // fragment f of a chunk = (k step f / MTA, row tile f % MTA of this wave's half, clamped to a real tile)
@@ -233,8 +236,6 @@ __global__ __launch_bounds__(256) void gemm_bf16_large_kernel(const bf16_t *__re
         for (int ci = 0; ci < 2; ++ci) {          // two chunks = one revolution of the weight ring
             const int c = cb + ci;
             const int buf = ci;                   // chunks alternate buffers starting from buffer 0 at c0
-            load_a(c + 1);
-            __builtin_amdgcn_sched_barrier(0);
             bf16x8 af[AFD + 1];
 #pragma unroll
             for (int f = 0; f < AFD; ++f) af[f] = lds_frag(buf, f);
@@ -245,65 +246,82 @@ __global__ __launch_bounds__(256) void gemm_bf16_large_kernel(const bf16_t *__re
                 const int slot = ci * KS + ks;
 #pragma unroll
                 for (int j = 0; j < NT; ++j)
-                    acc[mt][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[f % (AFD + 1)], wbuf[slot][j], acc[mt][j],
-                                                                         0, 0, 0);
+                    acc[mt][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wbuf[slot][j], af[f % (AFD + 1)], acc[mt][j],
+                                                                         0, 0, 0);   // W first: acc = out^T
                 if (mt == MTA - 1) {              // this k step's ring slot is free again
 #pragma unroll
                     for (int j = 0; j < NT; ++j) wbuf[slot][j] = ld_w(j, c * KS + ks + PFK);
                 }
+                // the next chunk's A goes to the other LDS buffer one piece at a time between the MFMAs (a
+                // burst of stores would sit in front of the fragment reads in the in-order LDS queue), and
+                // the freed staging register at once takes the piece of the chunk after that
+                if ((f & 1) && (f >> 1) < STAGE) {
+                    store_a1(f >> 1, buf ^ 1);
+                    load_a1(f >> 1, c + 2);
+                }
                 __builtin_amdgcn_sched_barrier(0);    // pin the order: LDS prefetch, MFMAs, ring reload
             }
-            store_a(buf ^ 1);
             __syncthreads();
         }
     }
 
-    // ---- epilogue.  D lane l register e = row 8*(e/4) + 4*(l/32) + e%4, column l%32: a lane owns one column, so
-    // each 32x32 tile is turned through a private LDS patch (the staging buffers are free after the last
-    // barrier) and leaves as 16-byte pieces: 4 wide stores per tile instead of 16 narrow ones.
+    // ---- epilogue.  The weight fragment is the MFMA's first operand, so the accumulator holds the output tile
+    // transposed: lane l owns activation row l%32 of the row tile, and its register e is column
+    // 8*(e/4) + 4*(l/32) + e%4 of the 32-column tile.  Four consecutive registers are four consecutive columns of
+    // one row: they leave as one 16-byte store, with no trip through LDS.
     const int lq = lane & 31, lh = lane >> 5;
     if (epi == GEMM_EPI_SWIGLU) {
         // columns 0-15 of a tile are gate, 16-31 up, of the same 16 features (tile T = features 16T..16T+15 =
-        // exactly one k step of the next GEMM's A-fragment layout): h = silu(gate) * up, stored as one fragment
-        bf16_t *hs = reinterpret_cast<bf16_t *>(gemm_smem) + wave * (32 * 16);
+        // exactly one k step of the next GEMM's A-fragment layout), so gate and up of a feature sit in the same
+        // lane, 8 registers apart: h = silu(gate) * up needs no shuffle.  A lane then holds features 4*(l/32)+0..3
+        // and 8+4*(l/32)+0..3 of its row; the fragment wants 8*(l/32)+0..7.  One half-wave swap fixes that: the
+        // upper lanes hand their features 4-7 to the lower lanes and take the lower lanes' 8-11.
         bf16_t *ho = reinterpret_cast<bf16_t *>(out);
+        typedef bf16_t bf16x2 __attribute__((ext_vector_type(2)));
 #pragma unroll
         for (int mt = 0; mt < MTA; ++mt) {
             const int tile_r = mh * MTA + mt;
 #pragma unroll
             for (int j = 0; j < NT; ++j) {
+                unsigned pk[4];
 #pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const float v = acc[mt][j][e];
-                    const float u = __shfl_xor(v, 16);
-                    if (lq < 16)
-                        hs[(8 * (e >> 2) + 4 * lh + (e & 3)) * 16 + lq] = (bf16_t)(v / (1.f + __expf(-v)) * u);
+                for (int i = 0; i < 8; i += 2) {
+                    float h2[2];
+#pragma unroll
+                    for (int t = 0; t < 2; ++t) {
+                        const float g = acc[mt][j][i + t], u = acc[mt][j][i + t + 8];
+                        h2[t] = g * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-1.4426950408889634f * g)) * u;
+                    }
+                    bf16x2 b;
+                    b[0] = (bf16_t)h2[0];
+                    b[1] = (bf16_t)h2[1];
+                    pk[i >> 1] = __builtin_bit_cast(unsigned, b);
                 }
-                const bf16x8 piece = *(const bf16x8 *)(hs + lq * 16 + 8 * lh);
+                // pk[0..1]: features 4*lh + 0..3; pk[2..3]: features 8 + 4*lh + 0..3
+                const auto s0 = __builtin_amdgcn_permlane32_swap(pk[0], pk[2], false, false);
+                const auto s1 = __builtin_amdgcn_permlane32_swap(pk[1], pk[3], false, false);
+                typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+                const u32x4 piece = {s0[0], s1[0], s0[1], s1[1]};
                 if (tile_r < ct_here && tile0 + j < t32)
-                    *(bf16x8 *)(ho + (((size_t)(tile0 + j) * m_tiles + mt_base + tile_r) * 64 + lane) * 8) = piece;
+                    *(u32x4 *)(ho + (((size_t)(tile0 + j) * m_tiles + mt_base + tile_r) * 64 + lane) * 8) = piece;
             }
         }
         return;
     }
-    float *scr = reinterpret_cast<float *>(gemm_smem) + wave * (32 * 36);
     float *o = out + (size_t)blockIdx.y * M * N;
 #pragma unroll
     for (int mt = 0; mt < MTA; ++mt) {
         const int tile_r = mh * MTA + mt;
         if (tile_r >= ct_here) continue;          // also drops the repeated tile (wave-uniform)
+        const int row = (mt_base + tile_r) * 32 + lq;
 #pragma unroll
         for (int j = 0; j < NT; ++j) {
 #pragma unroll
-            for (int e = 0; e < 16; ++e) scr[(8 * (e >> 2) + 4 * lh + (e & 3)) * 36 + lq] = acc[mt][j][e];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int idx = lane + 64 * i;
-                const int r = idx >> 3, c4 = idx & 7;
-                const f32x4 v = *(const f32x4 *)(scr + r * 36 + 4 * c4);
-                const int row = (mt_base + tile_r) * 32 + r;
-                const int col = (tile0 + j) * 32 + 4 * c4;
+            for (int g = 0; g < 4; ++g) {
+                const int col = (tile0 + j) * 32 + 8 * g + 4 * lh;
                 if (row < M && col < N) {
+                    const f32x4 v = {acc[mt][j][4 * g], acc[mt][j][4 * g + 1], acc[mt][j][4 * g + 2],
+                                     acc[mt][j][4 * g + 3]};
                     const size_t oi = (epi == GEMM_EPI_ROWMAJOR) ? (size_t)row * N + col
                                                                  : ((size_t)(col >> 4) * M + row) * 16 + (col & 15);
                     *(f32x4 *)(o + oi) = v;
