@@ -212,16 +212,24 @@ __global__ __launch_bounds__(256) void gemm_bf16_large_kernel(const bf16_t *__re
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
     bf16x8 wbuf[PFK][NT];
+    // The loads of the ring's second half and of the second chunk's A are issued in the order the loop issues
+    // them, so that the in-flight counts the compiler derives at the loop entry equal those of the back edge.
 #pragma unroll
     for (int s = 0; s < STAGE; ++s) load_a1(s, c0);
 #pragma unroll
-    for (int s = 0; s < PFK; ++s)
+    for (int s = 0; s < KS; ++s)
 #pragma unroll
         for (int j = 0; j < NT; ++j) wbuf[s][j] = ld_w(j, q0 + s);
 #pragma unroll
-    for (int s = 0; s < STAGE; ++s) {
-        store_a1(s, 0);
-        load_a1(s, c0 + 1);
+    for (int s = 0; s < STAGE; ++s) store_a1(s, 0);
+#pragma unroll
+    for (int f = 0; f < FR; ++f) {
+        if (f % MTA == MTA - 1) {
+#pragma unroll
+            for (int j = 0; j < NT; ++j) wbuf[KS + f / MTA][j] = ld_w(j, q0 + KS + f / MTA);
+        }
+        if ((f & 1) && (f >> 1) < STAGE) load_a1(f >> 1, c0 + 1);
+        __builtin_amdgcn_sched_barrier(0);
     }
     __syncthreads();
 
@@ -267,8 +275,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_large_kernel(const bf16_t *__re
 
     // ---- epilogue.  The weight fragment is the MFMA's first operand, so the accumulator holds the output tile
     // transposed: lane l owns activation row l%32 of the row tile, and its register e is column
-    // 8*(e/4) + 4*(l/32) + e%4 of the 32-column tile.  Four consecutive registers are four consecutive columns of
-    // one row: they leave as one 16-byte store, with no trip through LDS.
+    // 8*(e/4) + 4*(l/32) + e%4 of the 32-column tile: four consecutive registers are four consecutive columns of
+    // one row.
     const int lq = lane & 31, lh = lane >> 5;
     if (epi == GEMM_EPI_SWIGLU) {
         // columns 0-15 of a tile are gate, 16-31 up, of the same 16 features (tile T = features 16T..16T+15 =
@@ -308,20 +316,30 @@ __global__ __launch_bounds__(256) void gemm_bf16_large_kernel(const bf16_t *__re
         }
         return;
     }
+    // Partial sums and logits: a lane's four consecutive columns are 16 bytes, but neighbouring lanes are
+    // neighbouring rows, 64 bytes apart in the tiled layout.  Each tile is therefore turned through a per-wave
+    // LDS patch (16-byte writes, 16-byte reads; the staging buffers are free after the last barrier) so that four
+    // lanes together store one whole 64-byte run.
+    float *scr = reinterpret_cast<float *>(gemm_smem) + wave * (32 * 36);
     float *o = out + (size_t)blockIdx.y * M * N;
 #pragma unroll
     for (int mt = 0; mt < MTA; ++mt) {
         const int tile_r = mh * MTA + mt;
         if (tile_r >= ct_here) continue;          // also drops the repeated tile (wave-uniform)
-        const int row = (mt_base + tile_r) * 32 + lq;
 #pragma unroll
         for (int j = 0; j < NT; ++j) {
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int col = (tile0 + j) * 32 + 8 * g + 4 * lh;
+            for (int g = 0; g < 4; ++g)
+                *(f32x4 *)(scr + lq * 36 + 8 * g + 4 * lh) = (f32x4){acc[mt][j][4 * g], acc[mt][j][4 * g + 1],
+                                                                     acc[mt][j][4 * g + 2], acc[mt][j][4 * g + 3]};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int idx = lane + 64 * i;
+                const int r = idx >> 3, c4 = idx & 7;
+                const f32x4 v = *(const f32x4 *)(scr + r * 36 + 4 * c4);
+                const int row = (mt_base + tile_r) * 32 + r;
+                const int col = (tile0 + j) * 32 + 4 * c4;
                 if (row < M && col < N) {
-                    const f32x4 v = {acc[mt][j][4 * g], acc[mt][j][4 * g + 1], acc[mt][j][4 * g + 2],
-                                     acc[mt][j][4 * g + 3]};
                     const size_t oi = (epi == GEMM_EPI_ROWMAJOR) ? (size_t)row * N + col
                                                                  : ((size_t)(col >> 4) * M + row) * 16 + (col & 15);
                     *(f32x4 *)(o + oi) = v;
@@ -360,33 +378,38 @@ void launch_large(const bf16_t *a, const bf16_t *w, float *out, int M, int N, in
 // depends on (N, K) only.
 GemmPlan plan_gemm_bf16(int M, int N, int K, bool force_single_split) {
     GemmPlan p;
+    p.nt = 2;
+    p.bk = 128;
+    const int wgs = (N + 127) / 128;
+    const int units = (K + SPLIT_UNIT - 1) / SPLIT_UNIT;
+    auto fit = [&](int want) {                   // clamp to the units there are and drop empty trailing splits
+        want = want < 1 ? 1 : want > units ? units : want;
+        int per = (units + want - 1) / want;
+        return (units + per - 1) / per;
+    };
+    int splits = 1;
     if (M <= 32) {
         p.mt = M <= 16 ? 1 : 2;                  // 16-row tiles per wave (narrow kernel)
         p.m_chunks = 1;
+        // nearest count that brings the grid to about one wave of CUs
+        if (!force_single_split && wgs < 224) splits = fit((256 + wgs / 2) / wgs);
     } else {
-        int t = (M + 31) / 32;                   // 32-row tiles
-        p.mt = t <= 4 ? 2 : t <= 6 ? 3 : 5;      // per wave (wide kernel)
-        int ctl = p.mt == 5 ? 9 : 2 * p.mt;
+        // Partial sums are the expensive part of a split (each one is M x N floats written and read again), so
+        // the column blocks are split over K only until about half the CUs are busy; the rest of the chip is
+        // filled by cutting the rows into two workgroup passes, which costs a second read of W from L2 and no
+        // extra output.  The split count is a function of (N, K) alone: a row's sum is grouped the same way
+        // whatever the batch size.
+        if (!force_single_split) splits = fit(128 / wgs);
+        const int t = (M + 31) / 32;             // 32-row tiles
+        const bool row_split = !force_single_split && wgs * splits <= 128;
+        const int per_pass = row_split ? (t + 1) / 2 : t;
+        p.mt = per_pass <= 2 ? 1 : per_pass <= 4 ? 2 : per_pass <= 6 ? 3 : 5;      // per wave (wide kernel)
+        const int ctl = p.mt == 5 ? 9 : 2 * p.mt;
         p.m_chunks = (t + ctl - 1) / ctl;
-    }
-    p.nt = 2;
-    p.bk = 128;
-    int wgs = (N + 127) / 128;
-    int units = (K + SPLIT_UNIT - 1) / SPLIT_UNIT;
-    int splits = 1;
-    if (!force_single_split && wgs < 224) {
-        splits = (256 + wgs / 2) / wgs;          // nearest count that brings the grid to about one wave of CUs
-        if (splits > units) splits = units;
-        if (splits < 1) splits = 1;
-        int per = (units + splits - 1) / splits;
-        splits = (units + per - 1) / per;        // drop empty trailing splits
     }
     if (const char *e = getenv("TIDAR_GEMM_SPLITS")) {   // tuning override for sweeps (unset in normal use)
         int v = atoi(e);
-        if (v >= 1 && v <= units && !force_single_split) {
-            int per = (units + v - 1) / v;
-            splits = (units + per - 1) / per;
-        }
+        if (v >= 1 && !force_single_split) splits = fit(v);
     }
     p.splits = splits;
     return p;
@@ -397,6 +420,8 @@ void launch_gemm_bf16(const bf16_t *a, const bf16_t *w, float *out, int M, int N
     if (M <= 32) {
         if (p.mt == 1) launch_small<1, 16>(a, w, out, M, N, K, p, out_row_major, st);
         else launch_small<2, 8>(a, w, out, M, N, K, p, out_row_major, st);
+    } else if (p.mt == 1) {
+        launch_large<1>(a, w, out, M, N, K, p, out_row_major, st);
     } else if (p.mt == 2) {
         launch_large<2>(a, w, out, M, N, K, p, out_row_major, st);
     } else if (p.mt == 3) {

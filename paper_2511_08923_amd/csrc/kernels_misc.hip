@@ -1,6 +1,8 @@
 // Small kernels of the decode step: weight packing, row assembly + embedding gather, RMSNorm with fused
 // residual/split-K reduction, RoPE + K/V placement, SwiGLU, vocabulary argmax / Gumbel-max, verify/accept.
 // Also the fp32-mode GEMM and attention (plain ALU kernels used by the fp32 configuration).
+#include <stdlib.h>
+
 #include "tidar_internal.h"
 
 namespace {
@@ -131,7 +133,7 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(float *__restrict__ x, con
 }
 
 // ------------------------------------------------------------------ RoPE + K/V placement
-// One block per row.  qkv_part: tiled GEMM output, [S] x (q_dim + 2 kv_dim) columns.  Q rows -> q_out [M][q_dim];
+// blockIdx.x = row, blockIdx.y = slice of the row's work.  qkv_part: tiled GEMM output, [S] x (q_dim + 2 kv_dim) columns.  Q rows -> q_out [M][q_dim];
 // K/V of causal rows -> cache at position L + r; K/V of mask rows -> scratch tiles
 // k_scr [B][n_kv][n_mtiles][16][hd], v_scr [B][n_kv][n_mtiles][hd][16].
 template <typename T>
@@ -150,6 +152,7 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(const float *__restrict__ 
     auto val4 = [&](int col) {
         const float *pp = part + pt_index(col, row, M_all);
         float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll 4
         for (int sp = 0; sp < S; ++sp) {
             float4 q = *(const float4 *)(pp + (size_t)sp * split_stride);
             v.x += q.x; v.y += q.y; v.z += q.z; v.w += q.w;
@@ -163,13 +166,19 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(const float *__restrict__ 
         hi = make_float4(bb.x * c0.x + a.x * c0.y, bb.y * c0.z + a.y * c0.w, bb.z * c1.x + a.z * c1.y,
                          bb.w * c1.z + a.w * c1.w);
     };
-    for (int idx = threadIdx.x; idx < n_q * per_head; idx += blockDim.x) {
-        int h = idx / per_head, i = 4 * (idx - h * per_head);
-        float4 lo, hi;
-        rotate(val4(h * hd + i), val4(h * hd + i + half), i, lo, hi);
-        T *qo = q_out + (size_t)row * q_dim + h * hd + i;
-        store4<T>(qo, lo.x, lo.y, lo.z, lo.w);
-        store4<T>(qo + half, hi.x, hi.y, hi.z, hi.w);
+    // blockIdx.y: the first q_blocks workgroups of a row rotate Q (one item per thread), the rest place K/V
+    const int q_blocks = (n_q * per_head + blockDim.x - 1) / blockDim.x;
+    if ((int)blockIdx.y < q_blocks) {
+        const int idx = blockIdx.y * blockDim.x + threadIdx.x;
+        if (idx < n_q * per_head) {
+            int h = idx / per_head, i = 4 * (idx - h * per_head);
+            float4 lo, hi;
+            rotate(val4(h * hd + i), val4(h * hd + i + half), i, lo, hi);
+            T *qo = q_out + (size_t)row * q_dim + h * hd + i;
+            store4<T>(qo, lo.x, lo.y, lo.z, lo.w);
+            store4<T>(qo + half, hi.x, hi.y, hi.z, hi.w);
+        }
+        return;
     }
     // destination of this row's K/V
     const bool causal = r < d.nc;
@@ -187,7 +196,8 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(const float *__restrict__ 
     }
     T *kp = (T *)kv.k_pages;
     T *vp = (T *)kv.v_pages;
-    for (int idx = threadIdx.x; idx < n_kv * per_head; idx += blockDim.x) {
+    for (int idx = (blockIdx.y - q_blocks) * blockDim.x + threadIdx.x; idx < n_kv * per_head;
+         idx += (gridDim.y - q_blocks) * blockDim.x) {
         int h = idx / per_head, i = 4 * (idx - h * per_head);
         float4 lo, hi;
         rotate(val4(q_dim + h * hd + i), val4(q_dim + h * hd + i + half), i, lo, hi);
@@ -560,11 +570,11 @@ void launch_rmsnorm(int dtype, float *x, const float *part, int S, const void *g
     ActLayout mt_out = act_layout(rows);
     size_t stride = (size_t)M_all * d_model;
     if (dtype == TIDAR_BF16)
-        rmsnorm_kernel<bf16_t><<<rows, 256, 0, st>>>(x, part, S, stride, (const bf16_t *)gain, eps, R, row0, d_model,
-                                                      M_all, (bf16_t *)out, mt_out);
+        rmsnorm_kernel<bf16_t><<<rows, 256, 0, st>>>(x, part, S, stride, (const bf16_t *)gain, eps, R, row0,
+                                                          d_model, M_all, (bf16_t *)out, mt_out);
     else
         rmsnorm_kernel<float><<<rows, 256, 0, st>>>(x, part, S, stride, (const float *)gain, eps, R, row0, d_model,
-                                                     M_all, (float *)out, mt_out);
+                                                         M_all, (float *)out, mt_out);
 }
 
 void launch_gemm_f32(const float *a, const float *w, float *out, int M, int N, int K, int out_row_major,
@@ -590,11 +600,13 @@ void launch_rope_kv(int dtype, const float *qkv_part, int S, const float *rope_c
                     int B, int n_q, KvView kv, void *q_out, void *k_scr, void *v_scr, hipStream_t st) {
     int rows = B * d.R;
     size_t stride = (size_t)rows * (n_q + 2 * kv.n_kv) * kv.hd;
+    const int per_head = kv.hd / 8;                  // items (four rotation pairs) per head
+    dim3 grid(rows, (n_q * per_head + 255) / 256 + (kv.n_kv * per_head + 255) / 256);
     if (dtype == TIDAR_BF16)
-        rope_kv_kernel<bf16_t><<<rows, 256, 0, st>>>(qkv_part, S, stride, rope_cs, prefix_len, d, n_q, rows, kv,
+        rope_kv_kernel<bf16_t><<<grid, 256, 0, st>>>(qkv_part, S, stride, rope_cs, prefix_len, d, n_q, rows, kv,
                                                       (bf16_t *)q_out, (bf16_t *)k_scr, (bf16_t *)v_scr);
     else
-        rope_kv_kernel<float><<<rows, 256, 0, st>>>(qkv_part, S, stride, rope_cs, prefix_len, d, n_q, rows, kv,
+        rope_kv_kernel<float><<<grid, 256, 0, st>>>(qkv_part, S, stride, rope_cs, prefix_len, d, n_q, rows, kv,
                                                      (float *)q_out, (float *)k_scr, (float *)v_scr);
 }
 
