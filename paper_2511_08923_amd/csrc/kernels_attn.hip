@@ -59,24 +59,21 @@ typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 template <bool MASKED>
 __device__ inline void attn_block(const bf16_t *k_lds, const bf16_t *v_lds, int lq, int lh, const bf16x8 (&qf)[8],
                                   f32x16 (&acc)[4], float &m_run, float &l_run, float c, unsigned vis) {
-    // K as A operand (lane = key, hd half of the k step); fragments are consumed as they arrive
-    // two accumulation chains so that consecutive MFMAs do not wait on each other
-    f32x16 s, s2;
+    // K as A operand (lane = key, hd half of the k step); fragments are consumed as they arrive.  One
+    // accumulation chain: a second one costs 16 registers, and the other resident wave covers the dependency
+    f32x16 s;
 #pragma unroll
-    for (int e = 0; e < 16; ++e) s[e] = s2[e] = 0.f;
+    for (int e = 0; e < 16; ++e) s[e] = 0.f;
 #pragma unroll
-    for (int ks = 0; ks < 8; ks += 2) {
+    for (int ks = 0; ks < 8; ++ks) {
         const bf16x8 kf0 = *(const bf16x8 *)(k_lds + lq * K_STRIDE + 16 * ks + 8 * lh);
-        const bf16x8 kf1 = *(const bf16x8 *)(k_lds + lq * K_STRIDE + 16 * (ks + 1) + 8 * lh);
         s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf0, qf[ks], s, 0, 0, 0);
-        s2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf1, qf[ks + 1], s2, 0, 0, 0);
     }
+    // V^T as A operand (lane = d, key chunk): the first half is issued now and is needed after the softmax
+    // arithmetic; the second half is read once the scores are dead and takes over their registers
+    bf16x8 vf[2][2];
 #pragma unroll
-    for (int e = 0; e < 16; ++e) s[e] += s2[e];
-    // V^T as A operand (lane = d, key chunk): issued now, needed after the softmax arithmetic
-    bf16x8 vf[4][2];
-#pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
+    for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
         for (int u = 0; u < 2; ++u)
             vf[dt][u] = *(const bf16x8 *)(v_lds + (32 * dt + lq) * V_STRIDE + 16 * u + 8 * lh);
@@ -110,11 +107,22 @@ __device__ inline void attn_block(const bf16_t *k_lds, const bf16_t *v_lds, int 
         pf[e >> 3][(e & 7) + 1] = pk[1];
     }
     l_run += psum;
+    bf16x8 vg[2][2];
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
+    for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+            vg[dt][u] = *(const bf16x8 *)(v_lds + (32 * (dt + 2) + lq) * V_STRIDE + 16 * u + 8 * lh);
+#pragma unroll
+    for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
         for (int u = 0; u < 2; ++u)
             acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt][u], pf[u], acc[dt], 0, 0, 0);
+#pragma unroll
+    for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+            acc[dt + 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vg[dt][u], pf[u], acc[dt + 2], 0, 0, 0);
 }
 
 // QT: 32-row query tiles per wave.
@@ -249,24 +257,25 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
                 attn_block<false>(k_lds[buf], v_lds[buf], lq, lh, qf[i], acc[i], m_run[i], l_run[i], a.scale_log2e,
                                   0xffffu);
             } else {
-                // register e of unit u <-> key 8*((e/4)%2) + 4*lh + e%4 of that unit
+                // A row sees a contiguous key range of each unit: cache positions below L + vis, or the mask rows
+                // of its own block.  The range becomes a 16-bit mask over the unit's keys, from which the lane
+                // picks its eight: register e of unit u <-> key 8*((e/4)%2) + 4*lh + e%4 of that unit.
                 unsigned vis_bits = 0;                      // bit 8u+e: visible to this lane's query row
 #pragma unroll
                 for (int u = 0; u < 2; ++u) {
                     const int uu = 2 * it + u;
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        const int kin = 8 * (e >> 2) + 4 * lh + (e & 3);
-                        bool v = false;
-                        if (uu < n_cache_units) {
-                            const int pos = 16 * uu + kin;
-                            v = (pos < L) || (pos - L < r_vis[i]);
-                        } else if (uu < U) {
-                            const int m = 16 * (uu - n_cache_units) + kin;
-                            v = (m < n_mask) && (((m * a.inv_bl) >> 16) == r_blk[i]);
-                        }
-                        vis_bits |= (v ? 1u : 0u) << (8 * u + e);
+                    unsigned m16 = 0;
+                    if (uu < n_cache_units) {               // uniform
+                        const int lim = min(max(L + r_vis[i] - 16 * uu, 0), 16);
+                        m16 = (1u << lim) - 1u;
+                    } else if (uu < U) {
+                        const int m0 = 16 * (uu - n_cache_units);
+                        const int lo = min(max(r_blk[i] * d.bl - m0, 0), 16);
+                        const int hi = min(max(min((r_blk[i] + 1) * d.bl, n_mask) - m0, 0), 16);
+                        m16 = (r_blk[i] >= 0 && hi > lo) ? (((1u << hi) - 1u) & ~((1u << lo) - 1u)) : 0u;
                     }
+                    const unsigned v8 = ((m16 >> (4 * lh)) & 0xfu) | (((m16 >> (8 + 4 * lh)) & 0xfu) << 4);
+                    vis_bits |= v8 << (8 * u);
                 }
                 if (!__any(vis_bits != 0)) continue;        // nothing of this pair is visible to this tile
                 attn_block<true>(k_lds[buf], v_lds[buf], lq, lh, qf[i], acc[i], m_run[i], l_run[i], a.scale_log2e,
