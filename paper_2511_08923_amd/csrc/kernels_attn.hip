@@ -20,6 +20,8 @@
 // Keys come in units of 16: cache pages 0 .. ceil((L+nc)/16)-1, then the mask rows' scratch tiles.  Pages that
 // lie wholly below L need no mask at all (every row sees the whole prefix); everything else goes through the
 // (row, key) predicate and a per-(query tile, key pair) skip when nothing is visible.
+#include <stdlib.h>
+
 #include "tidar_internal.h"
 
 namespace {
@@ -332,18 +334,35 @@ __global__ __launch_bounds__(64) void attn_combine_kernel(const float *__restric
     const int f = hq * R + r;
     const int lane = threadIdx.x, d0 = 8 * (lane & 15), sl = lane >> 4;
     const size_t base = ((size_t)b * n_kv + g) * splits;
-    float mmax = -INFINITY;
-    for (int sp = 0; sp < splits; ++sp) mmax = fmaxf(mmax, mpart[(base + sp) * F + f]);
+    // reference of the whole row: lane s reads split s's (there are at most 64 splits), then a wave-wide maximum
+    float mmax = lane < splits ? mpart[(base + lane) * F + f] : -INFINITY;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) mmax = fmaxf(mmax, __shfl_xor(mmax, o));
     float num[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, den = 0.f;
-    for (int sp = sl; sp < splits; sp += 4) {
-        const float m = mpart[(base + sp) * F + f];
-        if (m == -INFINITY) continue;
-        const float wgt = exp2f(m - mmax);
-        const float *op = opart + ((base + sp) * F + f) * HD + d0;
-        const float4 a = *(const float4 *)op, c = *(const float4 *)(op + 4);
-        num[0] += wgt * a.x; num[1] += wgt * a.y; num[2] += wgt * a.z; num[3] += wgt * a.w;
-        num[4] += wgt * c.x; num[5] += wgt * c.y; num[6] += wgt * c.z; num[7] += wgt * c.w;
-        den += wgt * lpart[(base + sp) * F + f];
+    // four splits of this split lane at a time: all their loads are issued before the first is used (an absent
+    // split re-reads the last one and is given the weight of an empty split)
+    for (int sp0 = sl; sp0 < splits; sp0 += 16) {
+        float m[4], l[4];
+        float4 a[4], c[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int sp = sp0 + 4 * j;
+            const size_t pi = (base + min(sp, splits - 1)) * F + f;
+            m[j] = mpart[pi];
+            l[j] = lpart[pi];
+            const float *op = opart + pi * HD + d0;
+            a[j] = *(const float4 *)op;
+            c[j] = *(const float4 *)(op + 4);
+            if (sp >= splits) m[j] = -INFINITY;
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (m[j] == -INFINITY) continue;
+            const float wgt = exp2f(m[j] - mmax);
+            num[0] += wgt * a[j].x; num[1] += wgt * a[j].y; num[2] += wgt * a[j].z; num[3] += wgt * a[j].w;
+            num[4] += wgt * c[j].x; num[5] += wgt * c[j].y; num[6] += wgt * c[j].z; num[7] += wgt * c[j].w;
+            den += wgt * l[j];
+        }
     }
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
@@ -376,6 +395,10 @@ AttnPlan plan_attention(int B, int n_kv, int group, int R, int max_keys) {
     int cap = (iters + 3) / 4;                // at least four key pairs per split
     if (s > cap) s = cap;
     p.splits = s < 1 ? 1 : s;
+    if (const char *e = getenv("TIDAR_ATTN_SPLITS")) {     // tuning override for sweeps (unset in normal use)
+        int v = atoi(e);
+        if (v >= 1 && v <= 64) p.splits = v < cap ? v : (cap < 1 ? 1 : cap);
+    }
     return p;
 }
 

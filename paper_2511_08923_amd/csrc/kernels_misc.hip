@@ -97,7 +97,7 @@ __global__ void embed_rows_kernel(const T *__restrict__ embed, const int32_t *__
 // ------------------------------------------------------------------ residual add (split-K partials) + RMSNorm
 // One block per output row.  part: tiled GEMM output over M_all rows; out: A-fragment layout over the selected rows.
 template <typename T>
-__global__ __launch_bounds__(256) void rmsnorm_kernel(float *__restrict__ x, const float *__restrict__ part, int S,
+__global__ __launch_bounds__(1024) void rmsnorm_kernel(float *__restrict__ x, const float *__restrict__ part, int S,
                                                       size_t split_stride, const T *__restrict__ gain, float eps,
                                                       int R, int row0, int d_model, int M_all, T *__restrict__ out,
                                                       ActLayout lay) {
@@ -111,19 +111,31 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(float *__restrict__ x, con
         float4 v = *(const float4 *)(xr + c);
         if (S > 0) {
             const float *pp = part + pt_index(c, row, M_all);
-            for (int sp = 0; sp < S; ++sp) {
-                float4 q = *(const float4 *)(pp + (size_t)sp * split_stride);
+            int sp = 0;
+            for (; sp + 4 <= S; sp += 4) {         // four independent loads at a time, summed in split order
+                const float4 q0 = *(const float4 *)(pp + (size_t)sp * split_stride);
+                const float4 q1 = *(const float4 *)(pp + (size_t)(sp + 1) * split_stride);
+                const float4 q2 = *(const float4 *)(pp + (size_t)(sp + 2) * split_stride);
+                const float4 q3 = *(const float4 *)(pp + (size_t)(sp + 3) * split_stride);
+                v.x = (((v.x + q0.x) + q1.x) + q2.x) + q3.x;
+                v.y = (((v.y + q0.y) + q1.y) + q2.y) + q3.y;
+                v.z = (((v.z + q0.z) + q1.z) + q2.z) + q3.z;
+                v.w = (((v.w + q0.w) + q1.w) + q2.w) + q3.w;
+            }
+            for (; sp < S; ++sp) {
+                const float4 q = *(const float4 *)(pp + (size_t)sp * split_stride);
                 v.x += q.x; v.y += q.y; v.z += q.z; v.w += q.w;
             }
             *(float4 *)(xr + c) = v;
         }
         ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
     }
-    __shared__ float red[4];
+    __shared__ float red[16];
     ss = wave_sum(ss);
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
     __syncthreads();
-    const float tot = red[0] + red[1] + red[2] + red[3];
+    float tot = 0.f;
+    for (int w = 0; w < (int)(blockDim.x >> 6); ++w) tot += red[w];
     const float rs = rsqrtf(tot / (float)d_model + eps);
     for (int c = 4 * threadIdx.x; c < d_model; c += 4 * blockDim.x) {
         float4 v = *(const float4 *)(xr + c);          // this thread's own writes
@@ -569,11 +581,18 @@ void launch_rmsnorm(int dtype, float *x, const float *part, int S, const void *g
     int rows = B * (R - row0), M_all = B * R;
     ActLayout mt_out = act_layout(rows);
     size_t stride = (size_t)M_all * d_model;
+    // a row is one workgroup's only work: with few rows the chip is empty anyway, so a row gets as many threads
+    // as it has 4-column pieces (all of its loads in flight at once); with many rows 256 threads measured faster
+    int threads = 256;
+    if (rows <= 64) {
+        threads = ((d_model / 4 + 63) / 64) * 64;
+        threads = threads > 1024 ? 1024 : threads < 64 ? 64 : threads;
+    }
     if (dtype == TIDAR_BF16)
-        rmsnorm_kernel<bf16_t><<<rows, 256, 0, st>>>(x, part, S, stride, (const bf16_t *)gain, eps, R, row0,
+        rmsnorm_kernel<bf16_t><<<rows, threads, 0, st>>>(x, part, S, stride, (const bf16_t *)gain, eps, R, row0,
                                                           d_model, M_all, (bf16_t *)out, mt_out);
     else
-        rmsnorm_kernel<float><<<rows, 256, 0, st>>>(x, part, S, stride, (const float *)gain, eps, R, row0, d_model,
+        rmsnorm_kernel<float><<<rows, threads, 0, st>>>(x, part, S, stride, (const float *)gain, eps, R, row0, d_model,
                                                          M_all, (float *)out, mt_out);
 }
 
