@@ -149,12 +149,12 @@ __global__ __launch_bounds__(256) void gemm_bf16_small_kernel(const bf16_t *__re
 // ------------------------------------------------------------------ 32 < M: 32x32x16 MFMA, A through LDS, 2 x 2 waves
 // MTA: 32-row tiles per wave; the workgroup pass covers CTL row tiles (2*MTA, or 9 when MTA is 5: the second
 // row half then repeats a tile whose results are dropped).  Chunk of K = 128 (8 k steps); weight ring 16 k steps.
-template <int MTA>
+template <int MTA, bool WIDE>
 __global__ __launch_bounds__(256) void gemm_bf16_large_kernel(const bf16_t *__restrict__ a,
                                                               const bf16_t *__restrict__ w, float *__restrict__ out,
                                                               int M, int N, int K, int splits, int epi) {
     constexpr int NT = 2, KS = 8, PFK = 16;
-    constexpr int CTL = (MTA == 5) ? 9 : 2 * MTA;
+    constexpr int CTL = WIDE ? MTA : (MTA == 5) ? 9 : 2 * MTA;
     constexpr int PIECES = CTL * KS * 64;        // 16-byte pieces per chunk
     constexpr int STAGE = (PIECES + 255) / 256;
     constexpr int FR = KS * MTA;                 // A fragments a wave consumes per chunk
@@ -164,7 +164,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_large_kernel(const bf16_t *__re
     bf16x8 *lds = reinterpret_cast<bf16x8 *>(gemm_smem);      // [2][KS][CTL][64]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int mh = wave & 1, ng = wave >> 1;
+    const int mh = WIDE ? 0 : wave & 1, ng = WIDE ? wave : wave >> 1;
     const int t32 = (N + 31) >> 5, m_tiles = (M + 31) >> 5;
     const int mt_base = blockIdx.z * CTL;
     const int ct_here = min(CTL, m_tiles - mt_base);
@@ -172,7 +172,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_large_kernel(const bf16_t *__re
     const SplitRange sr32 = split_range(K, splits, blockIdx.y);
     const int q0 = sr32.q0 * 2, q1 = min(sr32.q1 * 2, q_total);
     const int c0 = q0 / KS, c1 = (q1 + KS - 1) / KS;
-    const int tile0 = (blockIdx.x * 2 + ng) * NT;              // first 32-column tile of this wave
+    const int tile0 = (blockIdx.x * (WIDE ? 4 : 2) + ng) * NT;   // first 32-column tile of this wave
     const __amdgpu_buffer_rsrc_t ra = make_rsrc(a, (size_t)q_total * m_tiles * 1024);
     const __amdgpu_buffer_rsrc_t rw = make_rsrc(w, (size_t)t32 * 32 * K * 2);
 
@@ -356,30 +356,30 @@ void launch_small(const bf16_t *a, const bf16_t *w, float *out, int M, int N, in
     gemm_bf16_small_kernel<MT, PFK><<<grid, 256, 0, st>>>(a, w, out, M, N, K, p.splits, row_major);
 }
 
-template <int MTA>
+template <int MTA, bool WIDE>
 void launch_large(const bf16_t *a, const bf16_t *w, float *out, int M, int N, int K, const GemmPlan &p, int epi,
                   hipStream_t st) {
-    constexpr int CTL = (MTA == 5) ? 9 : 2 * MTA;
+    constexpr int CTL = WIDE ? MTA : (MTA == 5) ? 9 : 2 * MTA;
+    constexpr int BN = WIDE ? 256 : 128;
     int m_tiles = (M + 31) / 32;
-    dim3 grid((N + 127) / 128, p.splits, (m_tiles + CTL - 1) / CTL);
+    dim3 grid((N + BN - 1) / BN, p.splits, (m_tiles + CTL - 1) / CTL);
     constexpr size_t SMEM = (size_t)2 * CTL * 8 * 1024;
     static bool attr_set = false;          // LDS above 64 KiB has to be granted per kernel
     if (!attr_set) {
-        (void)hipFuncSetAttribute((const void *)gemm_bf16_large_kernel<MTA>,
+        (void)hipFuncSetAttribute((const void *)gemm_bf16_large_kernel<MTA, WIDE>,
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)SMEM);
         attr_set = true;
     }
-    gemm_bf16_large_kernel<MTA><<<grid, 256, SMEM, st>>>(a, w, out, M, N, K, p.splits, epi);
+    gemm_bf16_large_kernel<MTA, WIDE><<<grid, 256, SMEM, st>>>(a, w, out, M, N, K, p.splits, epi);
 }
 
 }  // namespace
 
-// Every configuration covers 128 columns per workgroup, so the tile count, and with it the split-K plan,
-// depends on (N, K) only.
 GemmPlan plan_gemm_bf16(int M, int N, int K, bool force_single_split) {
     GemmPlan p;
     p.nt = 2;
     p.bk = 128;
+    p.wide = 0;
     const int wgs = (N + 127) / 128;
     const int units = (K + SPLIT_UNIT - 1) / SPLIT_UNIT;
     auto fit = [&](int want) {                   // clamp to the units there are and drop empty trailing splits
@@ -404,7 +404,17 @@ GemmPlan plan_gemm_bf16(int M, int N, int K, bool force_single_split) {
         const bool row_split = !force_single_split && wgs * splits <= 128;
         const int per_pass = row_split ? (t + 1) / 2 : t;
         p.mt = per_pass <= 2 ? 1 : per_pass <= 4 ? 2 : per_pass <= 6 ? 3 : 5;      // per wave (wide kernel)
-        const int ctl = p.mt == 5 ? 9 : 2 * p.mt;
+        int ctl = p.mt == 5 ? 9 : 2 * p.mt;
+        // many column blocks, one split, more than five row tiles: 256-column workgroups over five row tiles
+        // (four waves side by side, no weight fragment loaded twice) in two or more row passes.  Only when the
+        // whole grid is resident at once: the passes of a column block then run together and the second read
+        // of its weights hits L2 (measured on the LM head, whose grid takes several rounds: 30 % slower)
+        const int wide_wgs = ((N + 255) / 256) * ((t + 4) / 5);
+        if (splits == 1 && wgs >= 128 && t > 5 && wide_wgs <= 256) {
+            p.wide = 1;
+            p.mt = 5;
+            ctl = 5;
+        }
         p.m_chunks = (t + ctl - 1) / ctl;
     }
     if (const char *e = getenv("TIDAR_GEMM_SPLITS")) {   // tuning override for sweeps (unset in normal use)
@@ -420,13 +430,15 @@ void launch_gemm_bf16(const bf16_t *a, const bf16_t *w, float *out, int M, int N
     if (M <= 32) {
         if (p.mt == 1) launch_small<1, 16>(a, w, out, M, N, K, p, out_row_major, st);
         else launch_small<2, 8>(a, w, out, M, N, K, p, out_row_major, st);
+    } else if (p.wide) {
+        launch_large<5, true>(a, w, out, M, N, K, p, out_row_major, st);
     } else if (p.mt == 1) {
-        launch_large<1>(a, w, out, M, N, K, p, out_row_major, st);
+        launch_large<1, false>(a, w, out, M, N, K, p, out_row_major, st);
     } else if (p.mt == 2) {
-        launch_large<2>(a, w, out, M, N, K, p, out_row_major, st);
+        launch_large<2, false>(a, w, out, M, N, K, p, out_row_major, st);
     } else if (p.mt == 3) {
-        launch_large<3>(a, w, out, M, N, K, p, out_row_major, st);
+        launch_large<3, false>(a, w, out, M, N, K, p, out_row_major, st);
     } else {
-        launch_large<5>(a, w, out, M, N, K, p, out_row_major, st);
+        launch_large<5, false>(a, w, out, M, N, K, p, out_row_major, st);
     }
 }

@@ -97,6 +97,7 @@ struct GemmPlan {
     int splits;    // split-K factor
     int bk;        // K elements staged per LDS chunk
     int m_chunks;  // passes over M (grid.z)
+    int wide;      // 256-column workgroups (four waves side by side) instead of 128-column ones (2 x 2 waves)
 };
 
 GemmPlan plan_gemm_bf16(int M, int N, int K, bool force_single_split);
