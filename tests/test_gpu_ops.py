@@ -41,7 +41,12 @@ def _gemm(T, ctx, a, w):
 @pytest.mark.parametrize("M,N,K", [(1, 256, 512), (1, 4096, 4096), (3, 2048, 1536), (16, 1024, 8960), (20, 6144, 4096),
                                    (33, 528, 288), (72, 4096, 4096), (81, 1040, 1056), (144, 2048, 12288),
                                    (145, 784, 608), (272, 6144, 4096), (272, 4096, 12288), (272, 24576, 4096),
-                                   (273, 512, 256), (600, 1024, 1024)])
+                                   (273, 512, 256), (600, 1024, 1024),
+                                   # 256-column workgroups with a ragged last block and an odd 32-column tile count
+                                   (272, 16400, 512), (161, 16384, 256), (289, 32752, 384),
+                                   # row passes: 3 tiles as 2+1, 5 as 3+2, 7 as 4+3, 12 as 6+6; one tile (no row split)
+                                   (65, 4096, 2048), (160, 1536, 1536), (200, 4096, 1024), (384, 2048, 4096),
+                                   (40, 6144, 1024)])
 def test_gemm_matches_oracle_matmul(T, ctx8b, M, N, K):
     print(f"gemm M={M} N={N} K={K}", flush=True)
     a = TI.make_normal((M, K), seed=M * 7 + K, dtype=torch.bfloat16)
