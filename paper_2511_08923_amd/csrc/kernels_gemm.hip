@@ -20,7 +20,7 @@
 //   * a workgroup always covers 128 columns, and split-K over blockIdx.y works in units of 512 k: the split
 //     count depends on (N, K) only, never on M, so the partial-sum grouping of a row never depends on how many
 //     rows travel with it.
-//   * output: [split][16-column tile][row][16] fp32 (a tile is one contiguous block) or plain row-major for
+//   * output: [split][32-column tile][row][32] fp32 (a tile is one contiguous block) or plain row-major for
 //     the LM head; partials are summed in fixed order by the consumer.
 // 16x16x32: A lane l = row l%16, k slots 8*(l/16)..+7; B lane l = column l%16, same k slots; D lane l register i
 // = row 4*(l/16)+i, column l%16.   32x32x16: A lane l = row l%32, k slots 8*(l/32)..+7; B lane l = column l%32;
@@ -58,7 +58,7 @@ __device__ inline SplitRange split_range(int K, int splits, int split) {
 template <int MTW, int NT>
 __device__ inline void store_tiles(const f32x4 (&acc)[MTW][NT], float *out, int split, int M, int N, int tile0,
                                    int n_tiles, int mt0, int lane, int out_row_major) {
-    float *o = out + (size_t)split * M * N;
+    float *o = out + (size_t)split * pt_split_stride(M, N);
 #pragma unroll
     for (int mt = 0; mt < MTW; ++mt) {
         const int row0 = (mt0 + mt) * 16 + (lane >> 4) * 4;
@@ -71,7 +71,7 @@ __device__ inline void store_tiles(const f32x4 (&acc)[MTW][NT], float *out, int 
                 const int row = row0 + i;
                 if (row < M) {
                     size_t idx = out_row_major ? (size_t)row * N + tile * 16 + (lane & 15)
-                                               : ((size_t)tile * M + row) * 16 + (lane & 15);
+                                               : pt_index(tile * 16 + (lane & 15), row, M);
                     o[idx] = acc[mt][j][i];
                 }
             }
@@ -317,11 +317,11 @@ __global__ __launch_bounds__(256) void gemm_bf16_large_kernel(const bf16_t *__re
         return;
     }
     // Partial sums and logits: a lane's four consecutive columns are 16 bytes, but neighbouring lanes are
-    // neighbouring rows, 64 bytes apart in the tiled layout.  Each tile is therefore turned through a per-wave
-    // LDS patch (16-byte writes, 16-byte reads; the staging buffers are free after the last barrier) so that four
-    // lanes together store one whole 64-byte run.
+    // neighbouring rows, 128 bytes apart in the tiled layout.  Each tile is therefore turned through a per-wave
+    // LDS patch (16-byte writes, 16-byte reads; the staging buffers are free after the last barrier) so that eight
+    // lanes together store one whole row of the tile (128 bytes) and a store instruction covers 1 KiB in one run.
     float *scr = reinterpret_cast<float *>(gemm_smem) + wave * (32 * 36);
-    float *o = out + (size_t)blockIdx.y * M * N;
+    float *o = out + (size_t)blockIdx.y * pt_split_stride(M, N);
 #pragma unroll
     for (int mt = 0; mt < MTA; ++mt) {
         const int tile_r = mh * MTA + mt;
@@ -340,8 +340,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_large_kernel(const bf16_t *__re
                 const int row = (mt_base + tile_r) * 32 + r;
                 const int col = (tile0 + j) * 32 + 4 * c4;
                 if (row < M && col < N) {
-                    const size_t oi = (epi == GEMM_EPI_ROWMAJOR) ? (size_t)row * N + col
-                                                                 : ((size_t)(col >> 4) * M + row) * 16 + (col & 15);
+                    const size_t oi = (epi == GEMM_EPI_ROWMAJOR) ? (size_t)row * N + col : pt_index(col, row, M);
                     *(f32x4 *)(o + oi) = v;
                 }
             }

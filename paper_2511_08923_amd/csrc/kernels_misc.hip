@@ -409,13 +409,13 @@ __global__ void pack_act_kernel(const T *__restrict__ src, int M, int K, T *__re
     }
 }
 
-// tiled partial sums [S][N/16][M][16] -> plain row-major [M][N]
+// tiled partial sums [S][N/32][M][32] -> plain row-major [M][N]
 __global__ void untile_sum_kernel(const float *__restrict__ part, int S, int M, int N, float *__restrict__ out) {
-    size_t n = (size_t)M * N;
+    size_t n = (size_t)M * N, stride = pt_split_stride(M, N);
     for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < n; idx += (size_t)gridDim.x * blockDim.x) {
         int row = (int)(idx / N), col = (int)(idx % N);
         float v = 0.f;
-        for (int sp = 0; sp < S; ++sp) v += part[(size_t)sp * n + pt_index(col, row, M)];
+        for (int sp = 0; sp < S; ++sp) v += part[(size_t)sp * stride + pt_index(col, row, M)];
         out[idx] = v;
     }
 }
@@ -580,7 +580,7 @@ void launch_rmsnorm(int dtype, float *x, const float *part, int S, const void *g
                     int d_model, void *out, hipStream_t st) {
     int rows = B * (R - row0), M_all = B * R;
     ActLayout mt_out = act_layout(rows);
-    size_t stride = (size_t)M_all * d_model;
+    size_t stride = pt_split_stride(M_all, d_model);
     // a row is one workgroup's only work: with few rows the chip is empty anyway, so a row gets as many threads
     // as it has 4-column pieces (all of its loads in flight at once); with many rows 256 threads measured faster
     int threads = 256;
@@ -588,6 +588,7 @@ void launch_rmsnorm(int dtype, float *x, const float *part, int S, const void *g
         threads = ((d_model / 4 + 63) / 64) * 64;
         threads = threads > 1024 ? 1024 : threads < 64 ? 64 : threads;
     }
+    if (const char *e = getenv("TIDAR_RMS_THREADS")) threads = atoi(e);   // EXPERIMENT
     if (dtype == TIDAR_BF16)
         rmsnorm_kernel<bf16_t><<<rows, threads, 0, st>>>(x, part, S, stride, (const bf16_t *)gain, eps, R, row0,
                                                           d_model, M_all, (bf16_t *)out, mt_out);
@@ -618,7 +619,7 @@ void launch_untile_sum(const float *part, int S, int M, int N, float *out, hipSt
 void launch_rope_kv(int dtype, const float *qkv_part, int S, const float *rope_cs, const int32_t *prefix_len, RowDesc d,
                     int B, int n_q, KvView kv, void *q_out, void *k_scr, void *v_scr, hipStream_t st) {
     int rows = B * d.R;
-    size_t stride = (size_t)rows * (n_q + 2 * kv.n_kv) * kv.hd;
+    size_t stride = pt_split_stride(rows, (n_q + 2 * kv.n_kv) * kv.hd);
     const int per_head = kv.hd / 8;                  // items (four rotation pairs) per head
     dim3 grid(rows, (n_q * per_head + 255) / 256 + (kv.n_kv * per_head + 255) / 256);
     if (dtype == TIDAR_BF16)
@@ -650,7 +651,7 @@ void launch_attention_f32(const float *q, KvView kv, const float *k_scr, const f
 
 void launch_swiglu(int dtype, const float *part, int S, int M, int d_ff, void *out, hipStream_t st) {
     size_t n = (size_t)M * (d_ff / 4);
-    size_t stride = (size_t)M * 2 * d_ff;
+    size_t stride = pt_split_stride(M, 2 * d_ff);
     ActLayout mt = act_layout(M);
     if (dtype == TIDAR_BF16)
         swiglu_kernel<bf16_t><<<grid_for(n, 256, 8192), 256, 0, st>>>(part, S, stride, M, d_ff, (bf16_t *)out, mt);

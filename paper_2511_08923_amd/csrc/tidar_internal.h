@@ -64,10 +64,15 @@ __host__ __device__ inline size_t af_index(int row, int k, ActLayout a) {
     return ((((size_t)(k >> 5) * a.tiles + (row >> 4)) * 64) + ((k >> 3) & 3) * 16 + (row & 15)) * 8 + (k & 7);
 }
 __host__ __device__ inline size_t af_elems(int rows, int K) { return (size_t)((rows + 31) / 32) * 32 * K; }
-// Layout of every GEMM output except the logits: [split][16-column tile][row][16] fp32.
+// Layout of every GEMM output except the logits: [split][32-column tile][row][32] fp32.  A row's share of a tile
+// is one 128-byte cache line, so a consumer that owns a row never fetches a line it shares with another row's
+// consumer (with 16-column tiles every line was fetched twice, by two different XCDs).  N is padded to whole
+// tiles; the pad columns are never written or read.
+__host__ __device__ inline int pt_cols(int N) { return (N + 31) & ~31; }
 __host__ __device__ inline size_t pt_index(int n, int row, int M) {
-    return ((size_t)(n >> 4) * M + row) * 16 + (n & 15);
+    return ((size_t)(n >> 5) * M + row) * 32 + (n & 31);
 }
+__host__ __device__ inline size_t pt_split_stride(int M, int N) { return (size_t)M * pt_cols(N); }
 
 // Paged cache geometry of one layer.
 struct KvView {

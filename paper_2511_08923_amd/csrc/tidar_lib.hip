@@ -61,7 +61,7 @@ struct Layout {
 };
 
 size_t gemm_out_floats(const tidar_config &c, int M, int N, int K) {
-    if (c.dtype != TIDAR_BF16) return (size_t)M * N;
+    if (c.dtype != TIDAR_BF16) return pt_split_stride(M, N);
     // the split count depends on the row-tile class of M; taking the maximum over the class boundaries
     // below M keeps the size monotone in M
     const int bounds[5] = {16, 32, 80, 144, M};
@@ -69,7 +69,7 @@ size_t gemm_out_floats(const tidar_config &c, int M, int N, int K) {
     for (int i = 0; i < 5; ++i) {
         int m = bounds[i] < M ? bounds[i] : M;
         GemmPlan p = plan_gemm_bf16(m, N, K, false);
-        size_t v = (size_t)p.splits * m * N;
+        size_t v = (size_t)p.splits * pt_split_stride(m, N);
         if (v > best) best = v;
     }
     return best;
@@ -559,7 +559,7 @@ tidar_status tidar_hybrid_attention(tidar_ctx *ctx, const tidar_kv_cache *kv, in
 size_t tidar_gemm_workspace_bytes(int32_t dtype, int32_t M, int32_t N, int32_t K) {
     if (M < 1 || N < 16 || K < 8) return 256;
     int splits = dtype == TIDAR_BF16 ? plan_gemm_bf16(M, N, K, false).splits : 1;
-    return align_up(af_elems(M, K) * esize(dtype)) + align_up((size_t)splits * M * N * 4);
+    return align_up(af_elems(M, K) * esize(dtype)) + align_up((size_t)splits * pt_split_stride(M, N) * 4);
 }
 
 tidar_status tidar_gemm(tidar_ctx *ctx, const void *a, const void *w_packed, float *out, int32_t M, int32_t N,
