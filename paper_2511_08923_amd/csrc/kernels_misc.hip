@@ -582,13 +582,12 @@ void launch_rmsnorm(int dtype, float *x, const float *part, int S, const void *g
     ActLayout mt_out = act_layout(rows);
     size_t stride = pt_split_stride(M_all, d_model);
     // a row is one workgroup's only work: with few rows the chip is empty anyway, so a row gets as many threads
-    // as it has 4-column pieces (all of its loads in flight at once); with many rows 256 threads measured faster
+    // as it has 4-column pieces (all of its loads in flight at once); with many rows the count measured no difference
     int threads = 256;
     if (rows <= 64) {
         threads = ((d_model / 4 + 63) / 64) * 64;
         threads = threads > 1024 ? 1024 : threads < 64 ? 64 : threads;
     }
-    if (const char *e = getenv("TIDAR_RMS_THREADS")) threads = atoi(e);   // EXPERIMENT
     if (dtype == TIDAR_BF16)
         rmsnorm_kernel<bf16_t><<<rows, threads, 0, st>>>(x, part, S, stride, (const bf16_t *)gain, eps, R, row0,
                                                           d_model, M_all, (bf16_t *)out, mt_out);
