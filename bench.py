@@ -43,6 +43,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch every kernel from the host instead of replaying "
                     "a captured HIP graph of the step")
+    ap.add_argument("--attn-bench", action="store_true",
+                    help="time the hybrid-mask attention call alone (TiDAR shape and 1-row AR shape) at --prefix/--k")
     ap.add_argument("--sweep", action="store_true",
                     help="latency table instead of the headline line: TiDAR step vs 1-token AR step for batch in "
                          "--sweep-batches and k in --sweep-ks at a synthetic cache of --prefix tokens per sequence "
@@ -87,6 +89,73 @@ def cpu_baseline(shape, k, L, mean_accept):
                       f"2-layer {shape.name} models ({t1:.2f} s, {t2:.2f} s), extrapolated linearly to "
                       f"{shape.n_layers} layers = {full:.1f} s/step, at {mean_accept} tokens/step",
             "step_s": full}
+
+
+def read_traffic_summary(shape_name, k, prefix):
+    """HBM bytes per GEMM launch measured with rocprofv3 --pmc (FETCH_SIZE and WRITE_SIZE runs, scaled by a copy of
+    known size): counters cannot be collected from inside this process, so the figure comes from the committed
+    summary of those runs for this workload (line 'traffic_bytes_per_launch: N'), or is null when there is none."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles",
+                        f"gemm_traffic_{shape_name}_k{k}_prefix{prefix}_pmc.md")
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("traffic_bytes_per_launch:"):
+                    return float(line.split(":")[1]), os.path.relpath(path, os.path.dirname(os.path.abspath(__file__)))
+    except OSError:
+        pass
+    return None, None
+
+
+def attention_microbench(args, torch, T, TI, dev):
+    """The hybrid-mask attention call alone at the 8B head geometry: 32 query / 8 kv heads, head_dim 128, a prefix
+    of --prefix tokens in shuffled 16-token pages, k = --k (TiDAR shape, k(k+1) rows) and the 1-row AR shape.
+    Sixteen distinct caches are rotated so that K/V comes from HBM, not from a cache level."""
+    sh = TI.SHAPE_8B.with_layers(1)
+    L, n_q, n_kv, hd = args.prefix, sh.n_q_heads, sh.n_kv_heads, sh.head_dim
+    ctx = T.tidar_create(T.make_config(sh, T.TIDAR_BF16, max_k=max(args.k, 1), max_batch=1))
+    pps = (L + args.k + 15) // 16 + 1
+    nbuf = 16
+    g = torch.Generator(device=dev)
+    g.manual_seed(42)
+    kps = [torch.randn(1, pps, n_kv, 16 * hd, device=dev, generator=g).bfloat16() for _ in range(nbuf)]
+    vps = [torch.randn(1, pps, n_kv, 16 * hd, device=dev, generator=g).bfloat16() for _ in range(nbuf)]
+    table = torch.randperm(pps, device=dev, generator=g).int().view(1, pps)
+    plen = torch.tensor([L], dtype=torch.int32, device=dev)
+    ws = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+    out = {}
+    for name, (nc, nb, bl, cond0) in (("tidar", (args.k, args.k, args.k, 1)), ("ar", (1, 0, 1, 1))):
+        R = nc + nb * bl
+        q = torch.randn(1, R, n_q, hd, device=dev, generator=g).bfloat16()
+        kn = torch.randn(1, R, n_kv, hd, device=dev, generator=g).bfloat16()
+        vn = torch.randn(1, R, n_kv, hd, device=dev, generator=g).bfloat16()
+        o = torch.empty(1, R, n_q, hd, dtype=torch.bfloat16, device=dev)
+
+        def call(i):
+            kv = T.tidar_kv_cache(kps[i % nbuf].data_ptr(), vps[i % nbuf].data_ptr(), table.data_ptr(), pps, pps)
+            T.tidar_hybrid_attention(ctx, kv, 0, 1, plen, q, kn, vn, nc, nb, bl, cond0, o, L, ws)
+
+        for i in range(args.warmup):
+            call(i)
+        torch.cuda.synchronize()
+        T.tidar_profile_reset(ctx)
+        T.tidar_profile_enable(ctx, True)
+        for i in range(args.steps):
+            call(i)
+        torch.cuda.synchronize()
+        pr = T.tidar_profile_read(ctx)
+        T.tidar_profile_enable(ctx, False)
+        us = {n: pr[n]["ms"] / pr[n]["launches"] * 1e3 for n in ("place_kv", "attention", "attention_combine") if n in pr}
+        allowed_new = nc * (nc + 1) // 2 + nb * bl * (cond0 - 1) + nb * bl * (nb + 1) // 2 + nb * bl * bl
+        flops = 4.0 * n_q * hd * (R * L + allowed_new)
+        kv_bytes = 2.0 * L * n_kv * hd * 2
+        t = us["attention"] + us.get("attention_combine", 0.0)
+        out[name] = {"rows": R, "prefix_len": L, "kernel_us": us, "attention_plus_combine_us": t,
+                     "tflops": flops / t / 1e6, "mfma_frac": flops / t / 1e6 / MFMA_BF16_PEAK_TFLOPS,
+                     "kv_GBs": kv_bytes / t / 1e3, "hbm_frac": kv_bytes / t / 1e3 / HBM_PEAK_GBS}
+    T.tidar_destroy(ctx)
+    print(json.dumps({"attention_microbench": out, "steps": args.steps, "warmup": args.warmup, "dtype": "bf16",
+                      "data": "synthetic N(0,1) Q/K/V, 16 rotating caches, shuffled page table"}))
 
 
 def sweep(args, shape, torch, T, TI, dev):
@@ -191,6 +260,8 @@ def main():
     shape = TI.SHAPES[args.shape]
     if args.layers != shape.n_layers:
         shape = shape.with_layers(args.layers)
+    if args.attn_bench:
+        return attention_microbench(args, torch, T, TI, dev)
     if args.sweep:
         return sweep(args, shape, torch, T, TI, dev)
     k, P, V = args.k, args.prefix, shape.vocab
@@ -299,6 +370,21 @@ def main():
     step_ms = t_tidar / args.steps * 1e3
     forced_ok = bool((counts == acc_len[args.warmup:args.warmup + args.steps]).all())
 
+    # ---- per-step latency spread: the same steps once more, an event pair around each replay (kept out of the
+    # timed region above so that the headline number has no events inside it)
+    reset()
+    run_steps(args.warmup, 0)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    fn = stepper(False)
+    for e0, e1 in evs:
+        e0.record()
+        fn()
+        e1.record()
+    torch.cuda.synchronize()
+    per_step = sorted(e0.elapsed_time(e1) for e0, e1 in evs)
+    pct = lambda q: per_step[min(len(per_step) - 1, int(q * len(per_step)))]
+    step_pcts = {"p10": pct(0.10), "p50": pct(0.50), "p90": pct(0.90)}
+
     # ---- full acceptance (drafts = the true continuation): upper bound k tokens per step
     reset()
     run_steps(min(args.warmup, 3), 0, full=True)
@@ -379,12 +465,15 @@ def main():
     bytes_per_launch = wbytes / launches_per_step
     achieved = bytes_per_launch / (gemm_launch_ms * 1e-3) / 1e9
     gemm_flops = 2.0 * R * (wbytes / 2)
-    traffic = None
+    traffic, traffic_source = None, None
     if args.traffic_kib:
         f, wr = [float(x) for x in args.traffic_kib.split(",")]
-        traffic = (f + wr) * 1024.0
+        traffic, traffic_source = (f + wr) * 1024.0, "--traffic-kib"
+    else:
+        traffic, traffic_source = read_traffic_summary(shape.name, k, P)
     roofline = {"bound": "hbm", "kernel": "gemm_bf16_kernel (all projections + LM head)", "achieved": achieved,
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                "traffic_source": traffic_source,
                 "bytes_per_launch": bytes_per_launch, "avg_launch_ms": gemm_launch_ms,
                 "launches_per_step": launches_per_step,
                 "mfma_tflops": gemm_flops / (gemm_ms_per_step * 1e-3) / 1e12,
@@ -399,7 +488,7 @@ def main():
         "config": {"workload": f"{shape.name} TiDAR decode, batch 1, k={k} ({R} rows/step), prompt {P} random tokens, "
                                f"greedy, acceptance lengths seeded with mean {args.mean_accept} (paper Table 2, 8B)",
                    "k": k, "prefix_len": P, "batch": 1, "layers": shape.n_layers},
-        "tidar_step_ms": step_ms, "ar_step_ms": ar_ms, "tidar_over_ar_latency": step_ms / ar_ms,
+        "tidar_step_ms": step_ms, "tidar_step_ms_percentiles": step_pcts, "ar_step_ms": ar_ms, "tidar_over_ar_latency": step_ms / ar_ms,
         "ar_tokens_per_s": 1e3 / ar_ms, "tokens_per_step": tokens / args.steps,
         "speedup_vs_ar_tokens_per_s": (tokens / t_tidar) / (1e3 / ar_ms),
         "forced_acceptance_reproduced": forced_ok,
