@@ -58,6 +58,44 @@ __device__ inline SplitRange split_range(int K, int splits, int split) {
 template <int MTW, int NT>
 __device__ inline void store_tiles(const f32x4 (&acc)[MTW][NT], float *out, int split, int M, int N, int tile0,
                                    int n_tiles, int mt0, int lane, int out_row_major) {
+    if (out_row_major == GEMM_EPI_ARGMAX) {
+        // lane l holds rows 4*(l/16)+i of a 16-row tile and column l%16 of each of its NT 16-column tiles: the
+        // larger of its columns per row, then the 16 lanes of a row group are folded (ties: lowest column)
+        const int G = ((N >> 4) + 1) >> 1;
+        float *pmax = out;
+        int *pidx = (int *)(out + (size_t)G * M);
+#pragma unroll
+        for (int mt = 0; mt < MTW; ++mt) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                float best = -INFINITY;
+                int bi = (tile0 << 4) + (lane & 15);
+#pragma unroll
+                for (int j = 0; j < NT; ++j) {
+                    const float v = acc[mt][j][i];
+                    if (tile0 + j < n_tiles && v > best) {
+                        best = v;
+                        bi = ((tile0 + j) << 4) + (lane & 15);
+                    }
+                }
+#pragma unroll
+                for (int o = 1; o < 16; o <<= 1) {
+                    const float ob = __shfl_xor(best, o);
+                    const int oi = __shfl_xor(bi, o);
+                    if (ob > best || (ob == best && oi < bi)) {
+                        best = ob;
+                        bi = oi;
+                    }
+                }
+                const int row = (mt0 + mt) * 16 + (lane >> 4) * 4 + i;
+                if ((lane & 15) == 0 && row < M) {
+                    pmax[(size_t)(tile0 >> 1) * M + row] = best;
+                    pidx[(size_t)(tile0 >> 1) * M + row] = bi;
+                }
+            }
+        }
+        return;
+    }
     float *o = out + (size_t)split * pt_split_stride(M, N);
 #pragma unroll
     for (int mt = 0; mt < MTW; ++mt) {
@@ -70,7 +108,7 @@ __device__ inline void store_tiles(const f32x4 (&acc)[MTW][NT], float *out, int 
             for (int i = 0; i < 4; ++i) {
                 const int row = row0 + i;
                 if (row < M) {
-                    size_t idx = out_row_major ? (size_t)row * N + tile * 16 + (lane & 15)
+                    size_t idx = out_row_major == GEMM_EPI_ROWMAJOR ? (size_t)row * N + tile * 16 + (lane & 15)
                                                : pt_index(tile * 16 + (lane & 15), row, M);
                     o[idx] = acc[mt][j][i];
                 }
@@ -312,6 +350,43 @@ __global__ __launch_bounds__(256) void gemm_bf16_large_kernel(const bf16_t *__re
                 const u32x4 piece = {s0[0], s1[0], s0[1], s1[1]};
                 if (tile_r < ct_here && tile0 + j < t32)
                     *(u32x4 *)(ho + (((size_t)(tile0 + j) * m_tiles + mt_base + tile_r) * 64 + lane) * 8) = piece;
+            }
+        }
+        return;
+    }
+    if (epi == GEMM_EPI_ARGMAX) {
+        // a lane walks its 32 columns of the wave's two tiles in rising order (strict > keeps the lowest column
+        // of a tie), then the two half-waves, which hold the same rows, are folded
+        const int G = (t32 + 1) >> 1;
+        float *pmax = out;
+        int *pidx = (int *)(out + (size_t)G * M);
+#pragma unroll
+        for (int mt = 0; mt < MTA; ++mt) {
+            const int tile_r = mh * MTA + mt;
+            if (tile_r >= ct_here) continue;      // wave-uniform
+            float best = -INFINITY;
+            int bi = tile0 * 32 + 4 * lh;
+#pragma unroll
+            for (int j = 0; j < NT; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int col = (tile0 + j) * 32 + 8 * (e >> 2) + 4 * lh + (e & 3);
+                    const float v = acc[mt][j][e];
+                    if (col < N && v > best) {
+                        best = v;
+                        bi = col;
+                    }
+                }
+            const float ob = __shfl_xor(best, 32);
+            const int oi = __shfl_xor(bi, 32);
+            if (ob > best || (ob == best && oi < bi)) {
+                best = ob;
+                bi = oi;
+            }
+            const int row = (mt_base + tile_r) * 32 + lq;
+            if (lh == 0 && row < M && tile0 < t32) {
+                pmax[(size_t)(tile0 >> 1) * M + row] = best;
+                pidx[(size_t)(tile0 >> 1) * M + row] = bi;
             }
         }
         return;

@@ -420,6 +420,53 @@ __global__ void untile_sum_kernel(const float *__restrict__ part, int S, int M, 
     }
 }
 
+// Fold of the LM head's per-group maxima ([G][M] values, then [G][M] columns).  A block takes RB rows (a power
+// of two, at most 16) and splits the groups over 1024 / RB slices; the slices are folded by a tree in LDS.  The
+// order (larger value, then lower column) is total, so the result does not depend on how the fold is grouped.
+__global__ __launch_bounds__(1024) void argmax_groups_kernel(const float *__restrict__ part, int M, int G, int RB,
+                                                             int32_t *__restrict__ y) {
+    const int r = threadIdx.x & (RB - 1), sl = threadIdx.x / RB, SL = 1024 / RB;
+    const int row = blockIdx.x * RB + r;
+    const float *pmax = part;
+    const int *pidx = (const int *)(part + (size_t)G * M);
+    float best = -INFINITY;
+    int bi = 0x7fffffff;
+    auto take = [&](float v, int i) {
+        if (v > best || (v == best && i < bi)) {
+            best = v;
+            bi = i;
+        }
+    };
+    if (row < M) {
+        int g = sl;
+        for (; g + 3 * SL < G; g += 4 * SL) {      // four independent loads at a time
+            const float v0 = pmax[(size_t)g * M + row], v1 = pmax[(size_t)(g + SL) * M + row];
+            const float v2 = pmax[(size_t)(g + 2 * SL) * M + row], v3 = pmax[(size_t)(g + 3 * SL) * M + row];
+            const int i0 = pidx[(size_t)g * M + row], i1 = pidx[(size_t)(g + SL) * M + row];
+            const int i2 = pidx[(size_t)(g + 2 * SL) * M + row], i3 = pidx[(size_t)(g + 3 * SL) * M + row];
+            take(v0, i0);
+            take(v1, i1);
+            take(v2, i2);
+            take(v3, i3);
+        }
+        for (; g < G; g += SL) take(pmax[(size_t)g * M + row], pidx[(size_t)g * M + row]);
+    }
+    __shared__ float sv[1024];
+    __shared__ int si[1024];
+    sv[threadIdx.x] = best;
+    si[threadIdx.x] = bi;
+    __syncthreads();
+    for (int half = SL >> 1; half >= 1; half >>= 1) {
+        if (sl < half) {
+            take(sv[threadIdx.x + half * RB], si[threadIdx.x + half * RB]);
+            sv[threadIdx.x] = best;
+            si[threadIdx.x] = bi;
+        }
+        __syncthreads();
+    }
+    if (sl == 0 && row < M) y[row] = bi == 0x7fffffff ? 0 : bi;
+}
+
 __global__ void set_i32_kernel(int32_t *p, int n, int32_t v) {
     int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) p[i] = v;
@@ -656,6 +703,12 @@ void launch_swiglu(int dtype, const float *part, int S, int M, int d_ff, void *o
         swiglu_kernel<bf16_t><<<grid_for(n, 256, 8192), 256, 0, st>>>(part, S, stride, M, d_ff, (bf16_t *)out, mt);
     else
         swiglu_kernel<float><<<grid_for(n, 256, 8192), 256, 0, st>>>(part, S, stride, M, d_ff, (float *)out, mt);
+}
+
+void launch_argmax_groups(const float *part, int M, int G, int32_t *y, hipStream_t st) {
+    int RB = 16;
+    while (RB > 1 && RB / 2 >= M) RB /= 2;       // smallest power of two that holds the rows, at most 16
+    argmax_groups_kernel<<<(M + RB - 1) / RB, 1024, 0, st>>>(part, M, G, RB, y);
 }
 
 void launch_argmax_rows(const float *logits, int B, int Rh, int vocab, int n_choose, const int32_t *pos_rows,

@@ -123,7 +123,12 @@ void launch_rmsnorm(int dtype, float *x, const float *part, int S, const void *g
 // Epilogue forms of the bf16 GEMM: tiled fp32 partial sums (default), plain row-major fp32 (the logits), or, for the
 // interleaved gate/up matrix with one split and M > 32, SwiGLU applied in registers and h written as bf16 straight
 // into the A-fragment layout of the down projection (out is then a bf16 buffer of af_elems(M, N/2)).
-enum { GEMM_EPI_TILED = 0, GEMM_EPI_ROWMAJOR = 1, GEMM_EPI_SWIGLU = 2 };
+enum { GEMM_EPI_TILED = 0, GEMM_EPI_ROWMAJOR = 1, GEMM_EPI_SWIGLU = 2, GEMM_EPI_ARGMAX = 3 };
+// GEMM_EPI_ARGMAX (single split): no output matrix; every wave reduces its columns to the largest value of each
+// row and the lowest column that holds it.  out is then [G][M] floats (values) followed by [G][M] ints (columns),
+// G = gemm_argmax_groups(M, N) column groups; launch_argmax_groups folds the groups (ties: lowest column).
+inline int gemm_argmax_groups(int M, int N) { return M <= 32 ? (N + 31) / 32 : (N + 63) / 64; }
+void launch_argmax_groups(const float *part, int M, int G, int32_t *y, hipStream_t st);
 void launch_gemm_bf16(const bf16_t *a, const bf16_t *w_packed, float *out, int M, int N, int K, const GemmPlan &p,
                       int epi, hipStream_t st);
 void launch_gemm_f32(const float *a, const float *w, float *out, int M, int N, int K, int out_row_major,

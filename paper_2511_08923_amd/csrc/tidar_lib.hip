@@ -56,7 +56,7 @@ inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 inline size_t esize(int dtype) { return dtype == TIDAR_BF16 ? 2 : 4; }
 
 struct Layout {
-    size_t pos, rope_cs, x, xn, gemm_out, q, k_scr, v_scr, attn_part, o, h, xh, logits, y, total;
+    size_t pos, rope_cs, x, xn, gemm_out, q, k_scr, v_scr, attn_part, o, h, xh, logits, logits_bytes, y, total;
     int attn_splits;
 };
 
@@ -114,7 +114,8 @@ Layout make_layout(const tidar_config &c, int B, int R, int n_mask, int Mh, int 
     l.o = take(af_elems(M, q_dim) * es);
     l.h = take(af_elems(M, c.d_ff) * es);
     l.xh = take(af_elems(Mh > 0 ? Mh : 1, c.d_model) * es);
-    l.logits = take(own_logits ? (size_t)(Mh > 0 ? Mh : 1) * c.vocab * 4 : 0);
+    l.logits_bytes = own_logits ? (size_t)(Mh > 0 ? Mh : 1) * c.vocab * 4 : 0;
+    l.logits = take(l.logits_bytes);
     l.y = take((size_t)(Mh > 0 ? Mh : 1) * 4);
     l.total = off;
     return l;
@@ -274,6 +275,21 @@ void forward_rows(tidar_ctx *ctx, const tidar_weights *w, const tidar_kv_cache *
         launch_rmsnorm(c.dtype, x, gout, S_prev, w->final_norm, c.rms_eps, B, d.R, head_row0, c.d_model, ws + l.xh, st);
     }
     float *logits = logits_dst ? logits_dst : (float *)(ws + l.logits);
+    // Greedy, AR-trusting, nobody asked for the logits: every row's answer is a plain argmax, which the LM head's
+    // epilogue forms per column group; the logits are never written.  (Its partial results fit the logits area:
+    // 8 bytes per row and 32 or 64 columns.)
+    if (c.dtype == TIDAR_BF16 && !logits_dst && !mode->sample && mode->beta == 1.0f && l.logits_bytes > 0) {
+        const int G = gemm_argmax_groups(Mh, c.vocab);
+        {
+            Prof p(ctx, KC_GEMM, st);
+            GemmPlan gp = plan_gemm_bf16(Mh, c.vocab, c.d_model, true);
+            launch_gemm_bf16((const bf16_t *)(ws + l.xh), (const bf16_t *)w->lm_head, logits, Mh, c.vocab, c.d_model,
+                             gp, GEMM_EPI_ARGMAX, st);
+        }
+        Prof p(ctx, KC_ARGMAX, st);
+        launch_argmax_groups(logits, Mh, G, (int32_t *)(ws + l.y), st);
+        return;
+    }
     int S = 1;
     gemm(ctx, ws + l.xh, w->lm_head, logits, Mh, c.vocab, c.d_model, true, &S, st);
     {

@@ -226,6 +226,44 @@ def test_small_bf16_teacher_forced_steps(T, small, k):
         d_o = nxt_o
 
 
+@pytest.mark.parametrize("k", [1, 4, 16])
+def test_bf16_fused_vocab_reduction_equals_logits_path(T, small, k):
+    """Greedy steps that do not ask for logits take the LM head's fused per-group argmax; with logits requested the
+    logits are written and reduced by the row kernel.  Same GEMM, same accumulators: tokens must be identical, and
+    equal to the lowest-index argmax of the returned logits (k = 1: the narrow GEMM kernel; 4, 16: the wide one;
+    the AR step covers a single row)."""
+    eng, _ = small
+    sh = TI.SMALL_GQA
+    P = 90
+    prompt = TI.make_prompt(sh, P, seed=77 + k)
+    first, _ = eng.prefill(prompt, k)
+    drafts = first.clone()
+    for step in range(3):
+        L = int(eng.prefix_len[0])
+        a1, acc1, nxt1, lg = eng.step(drafts, k, hint=L, want_logits=True)
+        torch.cuda.synchronize()
+        eng.prefix_len[:1].fill_(L)
+        a2, acc2, nxt2, _ = eng.step(drafts, k, hint=L)
+        torch.cuda.synchronize()
+        assert int(a1[0]) == int(a2[0])
+        assert acc1[0, :int(a1[0])].tolist() == acc2[0, :int(a2[0])].tolist()
+        assert nxt1[0].tolist() == nxt2[0].tolist()
+        y = lg[0].argmax(-1)                       # first occurrence = lowest index
+        a = int(a1[0])
+        assert int(nxt2[0, 0]) == int(y[a - 1])
+        if k > 1:
+            blk = k + (a - 1) * k
+            assert nxt2[0, 1:].tolist() == y[blk + 1:blk + k].tolist()
+        drafts = nxt2.clone()
+    L = int(eng.prefix_len[0])
+    t1, lg = eng.ar_step(drafts[:, 0].contiguous(), hint=L, want_logits=True)
+    torch.cuda.synchronize()
+    eng.prefix_len[:1].fill_(L)
+    t2, _ = eng.ar_step(drafts[:, 0].contiguous(), hint=L)
+    torch.cuda.synchronize()
+    assert int(t1[0]) == int(t2[0]) == int(lg[0].argmax())
+
+
 def test_small_bf16_device_tidar_vs_device_ar(T, small):
     """On-device check 3 in bf16: streams agree until a row whose top-2 margin is within rounding."""
     eng, model = small
