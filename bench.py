@@ -298,7 +298,18 @@ def main():
     stream[n_ref:n_ref + k] = nxt[0]                    # slot 0 is final, the rest only pads the gather below
 
     # ---- forced-acceptance drafts built on the device from the reference continuation
-    acc_len = TI.make_acceptance_lengths(k, n_timed, args.mean_accept, seed=6).to(dev)
+    acc_len = TI.make_acceptance_lengths(k, n_timed, args.mean_accept, seed=6)
+    # the seeded draws average close to the requested mean; nudge single steps by one until the timed window
+    # carries exactly round(mean * steps) tokens, so that the token count does not depend on --steps
+    want_total = int(round(args.mean_accept * args.steps))
+    i = 0
+    while int(acc_len[args.warmup:].sum()) != want_total and i < 64 * n_timed:
+        j = args.warmup + i % args.steps
+        d = 1 if int(acc_len[args.warmup:].sum()) < want_total else -1
+        if 1 <= int(acc_len[j]) + d <= k:
+            acc_len[j] += d
+        i += 1
+    acc_len = acc_len.to(dev)
     ar = torch.arange(k, device=dev, dtype=torch.int64)
 
     # Device-side step state, so that one step (draft synthesis + tidar_step) is a fixed launch sequence that
