@@ -60,33 +60,39 @@ def parse():
 
 
 def cpu_baseline(shape, k, L, mean_accept):
-    """Times the oracle as it stands on a bounded sample: one TiDAR step on 1- and 2-layer models of the
-    benchmark's shape, extrapolated linearly to the full depth."""
+    """Times the oracle as it stands on a bounded sample: TiDAR steps on 1- and 6-layer models of the benchmark's
+    shape (one untimed step to start the thread pool, then five timed ones each, about ten seconds of CPU work),
+    extrapolated linearly in the layer count to the full depth."""
     import torch
     import tidar_inputs as TI
     from oracle import tidar_oracle as O
+
+    reps = 5
 
     def one(n_layers):
         sh = shape.with_layers(n_layers)
         w = TI.make_weights(sh, seed=4, dtype=torch.bfloat16)
         model = O.OracleModel(sh, w, dtype=torch.float32, bf16_faithful=True)
-        st = model.new_state(L + 2 * k)
+        st = model.new_state(L + (reps + 2) * k)
         for l in range(n_layers):
             st.k[l][:L] = TI.make_normal((L, sh.n_kv_heads, sh.head_dim), 500 + l, torch.bfloat16).float()
             st.v[l][:L] = TI.make_normal((L, sh.n_kv_heads, sh.head_dim), 600 + l, torch.bfloat16).float()
         st.L = L
         drafts = [int(t) for t in TI.make_drafts(sh, k, seed=9)[0]]
+        _, _, drafts, _ = model.tidar_step(st, drafts)
         t0 = time.perf_counter()
-        model.tidar_step(st, drafts)
-        return time.perf_counter() - t0
+        for _ in range(reps):
+            _, _, drafts, _ = model.tidar_step(st, drafts)
+        return (time.perf_counter() - t0) / reps
 
-    t1, t2 = one(1), one(2)
-    per_layer = max(t2 - t1, 1e-9)
+    n_hi = min(6, shape.n_layers)
+    t1, t2 = one(1), one(n_hi)
+    per_layer = max((t2 - t1) / max(n_hi - 1, 1), 1e-9)
     head = max(t1 - per_layer, 0.0)
     full = head + per_layer * shape.n_layers
     return {"value": mean_accept / full, "unit": "tokens/s", "cores": torch.get_num_threads(), "kind": "oracle",
-            "sample": f"one oracle TiDAR step (k={k}, prefix {L}, fp32 accumulation, bf16 rounding points) on 1- and "
-                      f"2-layer {shape.name} models ({t1:.2f} s, {t2:.2f} s), extrapolated linearly to "
+            "sample": f"{reps} oracle TiDAR steps each (k={k}, prefix {L}, fp32 accumulation, bf16 rounding points) on 1- "
+                      f"and {n_hi}-layer {shape.name} models ({t1:.2f} s, {t2:.2f} s per step), extrapolated linearly to "
                       f"{shape.n_layers} layers = {full:.1f} s/step, at {mean_accept} tokens/step",
             "step_s": full}
 
