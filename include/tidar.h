@@ -222,6 +222,15 @@ tidar_status tidar_gemm(tidar_ctx *ctx, const void *a, const void *w_packed, flo
  * `cap` entries; the return value is the number of kernel classes seen.
  * Timing a whole step should be done with profiling off.
  */
+/* Block length for the coming steps (paper, Limitations, "Batch size": the block length can be changed between
+ * decode steps without retraining; Section 1 / Figure 1: a step costs about as much as a 1-token step while its
+ * rows fit the machine's free token slots).  Returns the largest k in {1, 2, 4, 8, 16} with
+ * k <= min(cfg.max_k, k_cap) and batch * k * (k + 1) <= row_budget.  row_budget <= 0 takes the library's figure
+ * for MI355X (160 rows: up to there the measured TiDAR step stays within about 1.4x of the 1-token step at the
+ * 8B shape); k_cap <= 0 means no cap.  Host only, no device work.  Returns 1 when nothing larger fits and 0 on
+ * invalid arguments (ctx NULL, batch < 1). */
+int32_t tidar_select_block_len(const tidar_ctx *ctx, int32_t batch, int32_t k_cap, int32_t row_budget);
+
 tidar_status tidar_profile_enable(tidar_ctx *ctx, int32_t on);
 int32_t      tidar_profile_read(tidar_ctx *ctx, const char **names, double *ms, int64_t *launches, int32_t cap);
 tidar_status tidar_profile_reset(tidar_ctx *ctx);

@@ -27,7 +27,7 @@ STATUS = {0: "TIDAR_OK", 1: "TIDAR_EINVAL", 2: "TIDAR_ENOMEM", 3: "TIDAR_ECAPACI
 EXPORTS = ["tidar_create", "tidar_destroy", "tidar_strerror", "tidar_packed_weight_bytes", "tidar_pack_weight",
            "tidar_workspace_bytes", "tidar_prefill", "tidar_step", "tidar_ar_step", "tidar_hybrid_attention",
            "tidar_gemm_workspace_bytes", "tidar_gemm", "tidar_profile_enable", "tidar_profile_read",
-           "tidar_profile_reset"]
+           "tidar_profile_reset", "tidar_select_block_len"]
 
 
 class TidarError(RuntimeError):
@@ -97,6 +97,8 @@ def _load() -> C.CDLL:
     lib.tidar_profile_read.restype = i32
     lib.tidar_profile_reset.argtypes = [vp]
     lib.tidar_profile_reset.restype = i32
+    lib.tidar_select_block_len.argtypes = [vp, i32, i32, i32]
+    lib.tidar_select_block_len.restype = i32
     return lib
 
 
@@ -196,6 +198,10 @@ def tidar_gemm(ctx, a: torch.Tensor, w_packed: torch.Tensor, out: torch.Tensor, 
 
 def tidar_profile_enable(ctx, on: bool) -> None:
     _check(_lib.tidar_profile_enable(ctx, 1 if on else 0), "tidar_profile_enable")
+
+
+def tidar_select_block_len(ctx, batch: int, k_cap: int = 0, row_budget: int = 0) -> int:
+    return int(_lib.tidar_select_block_len(ctx, batch, k_cap, row_budget))
 
 
 def tidar_profile_reset(ctx) -> None:

@@ -595,6 +595,17 @@ tidar_status tidar_gemm(tidar_ctx *ctx, const void *a, const void *w_packed, flo
     return TIDAR_OK;
 }
 
+int32_t tidar_select_block_len(const tidar_ctx *ctx, int32_t batch, int32_t k_cap, int32_t row_budget) {
+    if (!ctx || batch < 1) return 0;
+    const int budget = row_budget > 0 ? row_budget : 160;
+    int cap = ctx->cfg.max_k;
+    if (k_cap > 0 && k_cap < cap) cap = k_cap;
+    int best = 1;
+    for (int k = 2; k <= 16 && k <= cap; k *= 2)
+        if ((int64_t)batch * k * (k + 1) <= budget) best = k;
+    return best;
+}
+
 tidar_status tidar_profile_enable(tidar_ctx *ctx, int32_t on) {
     if (!ctx) return TIDAR_EINVAL;
     ctx->profiling = on != 0;

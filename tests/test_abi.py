@@ -95,3 +95,28 @@ def test_pack_weight_validation(T):
     assert T._lib.tidar_pack_weight(T.TIDAR_BF16, 8, 20, 64, 8, 32, 0, 1, None) == 1       # rows not multiple of 16
     assert T._lib.tidar_pack_weight(T.TIDAR_BF16, 8, 32, 48, 8, 32, 0, 1, None) == 1       # cols not multiple of 32
     assert T._lib.tidar_pack_weight(T.TIDAR_BF16, 8, 32, 64, 8, 32, 1, 1, None) == 1       # does not fit
+
+
+def test_select_block_len_follows_the_row_budget(T):
+    """Host-only policy: largest power-of-two block whose rows batch*k*(k+1) fit the budget (default 160 rows)."""
+    ctx = T.tidar_create(T.make_config(TI.SHAPE_8B, T.TIDAR_BF16, max_k=16, max_batch=32))
+    try:
+        assert T.tidar_select_block_len(ctx, 1) == 8            # 72 rows fit, 272 do not
+        assert T.tidar_select_block_len(ctx, 1, row_budget=272) == 16
+        assert T.tidar_select_block_len(ctx, 1, row_budget=271) == 8
+        assert T.tidar_select_block_len(ctx, 4) == 4            # 80 rows
+        assert T.tidar_select_block_len(ctx, 8) == 4            # 160 rows, exactly the budget
+        assert T.tidar_select_block_len(ctx, 9) == 2
+        assert T.tidar_select_block_len(ctx, 32) == 1           # 2*3*32 = 192 > 160
+        assert T.tidar_select_block_len(ctx, 1, k_cap=4, row_budget=10 ** 6) == 4
+        assert T.tidar_select_block_len(ctx, 0) == 0
+        assert T.tidar_select_block_len(None, 1) == 0
+        for batch in range(1, 40):                               # brute force over the definition
+            for budget in (1, 5, 20, 72, 160, 1000, 10 ** 5):
+                want = max([k for k in (1, 2, 4, 8, 16) if k == 1 or batch * k * (k + 1) <= budget])
+                assert T.tidar_select_block_len(ctx, batch, 0, budget) == want
+    finally:
+        T.tidar_destroy(ctx)
+    small = T.tidar_create(T.make_config(TI.TINY, T.TIDAR_F32, max_k=4))
+    assert T.tidar_select_block_len(small, 1, row_budget=10 ** 6) == 4   # never above the context's max_k
+    T.tidar_destroy(small)
