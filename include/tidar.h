@@ -222,6 +222,11 @@ tidar_status tidar_gemm(tidar_ctx *ctx, const void *a, const void *w_packed, flo
  * `cap` entries; the return value is the number of kernel classes seen.
  * Timing a whole step should be done with profiling off.
  */
+/* Causal rows per prefill pass (the prompt is prefilled in causal chunks through the step's kernels, the mask block
+ * of Appendix B joins the last chunk).  Default 1024; 1..4096.  Larger passes stream the weights fewer times and
+ * need a larger workspace: call before tidar_workspace_bytes.  Host only. */
+tidar_status tidar_set_prefill_chunk(tidar_ctx *ctx, int32_t rows);
+
 /* Block length for the coming steps (paper, Limitations, "Batch size": the block length can be changed between
  * decode steps without retraining; Section 1 / Figure 1: a step costs about as much as a 1-token step while its
  * rows fit the machine's free token slots).  Returns the largest k in {1, 2, 4, 8, 16} with

@@ -27,7 +27,7 @@ STATUS = {0: "TIDAR_OK", 1: "TIDAR_EINVAL", 2: "TIDAR_ENOMEM", 3: "TIDAR_ECAPACI
 EXPORTS = ["tidar_create", "tidar_destroy", "tidar_strerror", "tidar_packed_weight_bytes", "tidar_pack_weight",
            "tidar_workspace_bytes", "tidar_prefill", "tidar_step", "tidar_ar_step", "tidar_hybrid_attention",
            "tidar_gemm_workspace_bytes", "tidar_gemm", "tidar_profile_enable", "tidar_profile_read",
-           "tidar_profile_reset", "tidar_select_block_len"]
+           "tidar_profile_reset", "tidar_select_block_len", "tidar_set_prefill_chunk"]
 
 
 class TidarError(RuntimeError):
@@ -99,6 +99,8 @@ def _load() -> C.CDLL:
     lib.tidar_profile_reset.restype = i32
     lib.tidar_select_block_len.argtypes = [vp, i32, i32, i32]
     lib.tidar_select_block_len.restype = i32
+    lib.tidar_set_prefill_chunk.argtypes = [vp, i32]
+    lib.tidar_set_prefill_chunk.restype = i32
     return lib
 
 
@@ -200,6 +202,10 @@ def tidar_profile_enable(ctx, on: bool) -> None:
     _check(_lib.tidar_profile_enable(ctx, 1 if on else 0), "tidar_profile_enable")
 
 
+def tidar_set_prefill_chunk(ctx, rows: int) -> None:
+    _check(_lib.tidar_set_prefill_chunk(ctx, rows), "tidar_set_prefill_chunk")
+
+
 def tidar_select_block_len(ctx, batch: int, k_cap: int = 0, row_budget: int = 0) -> int:
     return int(_lib.tidar_select_block_len(ctx, batch, k_cap, row_budget))
 
@@ -234,7 +240,8 @@ class Engine:
 
     def __init__(self, shape, weights: Dict[str, object], dtype: int = TIDAR_BF16, max_k: int = 16,
                  max_batch: int = 1, max_seq_len: int = 1024, n_pages: Optional[int] = None,
-                 page_table: Optional[torch.Tensor] = None, device: str = "cuda:0", free_source: bool = False):
+                 page_table: Optional[torch.Tensor] = None, device: str = "cuda:0", free_source: bool = False,
+                 prefill_chunk: Optional[int] = None):
         if not torch.cuda.is_available():
             raise RuntimeError("the TiDAR HIP path needs a GPU; there is no CPU fallback")
         self.shape, self.dtype, self.device = shape, dtype, torch.device(device)
@@ -242,6 +249,8 @@ class Engine:
         self.max_k, self.max_batch, self.max_seq_len = max_k, max_batch, max_seq_len
         self.cfg = make_config(shape, dtype, max_k, max_batch)
         self.ctx = tidar_create(self.cfg)
+        if prefill_chunk is not None:
+            tidar_set_prefill_chunk(self.ctx, prefill_chunk)
         self._keep: List[torch.Tensor] = []
         self._pack_weights(weights, free_source)
         self.pages_per_seq = (max_seq_len + PAGE - 1) // PAGE

@@ -150,17 +150,29 @@ def test_tiny_fp32_other_block_lengths(T, tiny):
             assert int(a[0]) == a_o and d_g[0].tolist() == d_o
 
 
-def test_prefill_longer_than_one_chunk_fp32(T, tiny):
-    eng, model = tiny
+@pytest.mark.parametrize("chunk,P", [(64, 200), (48, 97), (1, 5), (200, 200), (None, 200)])
+def test_prefill_in_several_causal_passes_fp32(T, tiny, chunk, P):
+    """The library prefills in causal chunks (the mask block joins the last one): passes of 64 rows over 200 tokens
+    (three full + one ragged), of 48 over 97 (ragged tail of one row), of a single row, exactly one full chunk, and
+    the default chunk (one pass) all give the oracle's single-pass logits, first drafts and cache."""
+    _, model = tiny
+    sh = TI.TINY
+    w = TI.make_weights(sh, seed=1)
+    eng = T.Engine(sh, w, dtype=T.TIDAR_F32, max_k=4, max_batch=1, max_seq_len=256, prefill_chunk=chunk)
     k = 4
-    prompt = TI.make_prompt(TI.TINY, 200, seed=51)
-    # the library prefills in causal chunks; 200 < 256 is one pass, so also run a 2-pass case through a long prompt
-    for P in (200,):
-        st = model.new_state(256)
-        want_first, want_lg = model.prefill(st, [int(t) for t in prompt[0, :P]], k)
-        first, lg = eng.prefill(prompt[:, :P], k, want_logits=True)
-        assert float((lg[0].cpu().double() - want_lg).abs().max()) < 1e-4
-        assert first[0].tolist() == want_first
+    prompt = TI.make_prompt(sh, 200, seed=51)
+    st = model.new_state(256)
+    want_first, want_lg = model.prefill(st, [int(t) for t in prompt[0, :P]], k)
+    first, lg = eng.prefill(prompt[:, :P], k, want_logits=True)
+    torch.cuda.synchronize()
+    assert float((lg[0].cpu().double() - want_lg).abs().max()) < 1e-4
+    assert first[0].tolist() == want_first
+    assert int(eng.prefix_len[0]) == P
+    for l in range(sh.n_layers):
+        kk, vv = eng.read_cache(l, 0, P)
+        assert float((kk.cpu().double() - st.k[l][:P]).abs().max()) < 1e-4
+        assert float((vv.cpu().double() - st.v[l][:P]).abs().max()) < 1e-4
+    eng.close()
 
 
 # ----------------------------------------------------------------------------- bf16 MFMA path, small GQA model
@@ -264,6 +276,33 @@ def test_bf16_fused_vocab_reduction_equals_logits_path(T, small, k):
     assert int(t1[0]) == int(t2[0]) == int(lg[0].argmax())
 
 
+def test_small_bf16_long_prompt_two_default_passes(T):
+    """A 1100-token prompt at the default prefill chunk: one pass of 1024 causal rows (33 row tiles, several GEMM row
+    passes) and a last pass of 76 causal rows plus the mask block, against the oracle's single pass."""
+    sh = TI.SMALL_GQA
+    w = TI.make_weights(sh, seed=3, dtype=torch.bfloat16)
+    eng = T.Engine(sh, w, dtype=T.TIDAR_BF16, max_k=8, max_batch=1, max_seq_len=1280)
+    model = O.OracleModel(sh, w, bf16_faithful=True)
+    k, P = 8, 1100
+    prompt = TI.make_prompt(sh, P, seed=91)
+    st = model.new_state(1280)
+    d_o, lg_o = model.prefill(st, [int(t) for t in prompt[0]], k)
+    first, lg = eng.prefill(prompt, k, want_logits=True)
+    torch.cuda.synchronize()
+    err = float((lg[0].cpu().double() - lg_o).abs().max())
+    assert err < LOGIT_TOL, err
+    mis, bad = near_tie_mismatches(lg[0].cpu().argmax(-1), lg_o, err)
+    assert bad == 0
+    if mis == 0:
+        assert first[0].tolist() == d_o
+    assert int(eng.prefix_len[0]) == P
+    for l in range(sh.n_layers):
+        kk, vv = eng.read_cache(l, 0, P)
+        assert float((kk.cpu().double() - st.k[l][:P]).abs().max()) < 4e-2
+        assert float((vv.cpu().double() - st.v[l][:P]).abs().max()) < 4e-2
+    eng.close()
+
+
 def test_small_bf16_device_tidar_vs_device_ar(T, small):
     """On-device check 3 in bf16: streams agree until a row whose top-2 margin is within rounding."""
     eng, model = small
@@ -347,7 +386,7 @@ def test_1p5b_shape_two_layers_prefill_and_steps_vs_oracle(T):
     model: chunked prefill of a 300-token prompt (two passes), then teacher-forced steps at k = 16."""
     sh = TI.SHAPE_1P5B.with_layers(2)
     w = TI.make_weights(sh, seed=3, dtype=torch.bfloat16)
-    eng = T.Engine(sh, w, dtype=T.TIDAR_BF16, max_k=16, max_batch=1, max_seq_len=512)
+    eng = T.Engine(sh, w, dtype=T.TIDAR_BF16, max_k=16, max_batch=1, max_seq_len=512, prefill_chunk=256)
     model = O.OracleModel(sh, w, dtype=torch.float64, bf16_faithful=True)
     k, P = 16, 300
     prompt = TI.make_prompt(sh, P, seed=33)
