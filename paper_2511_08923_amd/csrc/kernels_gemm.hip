@@ -1,6 +1,6 @@
 // Skinny bf16 GEMM of the decode step: out = A[M][K] (bf16) x W[N][K]^T (bf16), fp32 accumulation.
 //
-// M is the step's row count (1 .. 272 per pass), N and K are model dimensions: every weight byte is used once
+// M is the step's row count (1 .. 272 at batch 1; more rows run as row passes), N and K are model dimensions: every weight byte is used once
 // per step, so the kernel is a weight streamer with MFMA attached.
 //   * W lives in HBM as the register image of the 32x32x16 MFMA B operand
 //     ([k step of 16][32-column tile][lane][8]); a wave's load of one fragment is one fully coalesced 1 KiB read
@@ -15,13 +15,18 @@
 //     sched_barrier pins each reload right behind the MFMAs that free its slot.
 //   * M <= 32: 16x16x32 MFMA (fewer pad rows), no LDS, no barriers; a wave streams its 32 columns and the A
 //     fragments through two register rings.  M > 32: 32x32x16 MFMA (on gfx950 it issues at twice the rate of
-//     16x16x32: measured 2.2 vs 1.2 PFLOP/s), 4 waves as a 2 x 2 grid (two row halves x two 64-column groups),
-//     A staged through LDS once per workgroup and prefetched into registers ahead of the MFMAs.
-//   * a workgroup always covers 128 columns, and split-K over blockIdx.y works in units of 512 k: the split
-//     count depends on (N, K) only, never on M, so the partial-sum grouping of a row never depends on how many
-//     rows travel with it.
-//   * output: [split][32-column tile][row][32] fp32 (a tile is one contiguous block) or plain row-major for
-//     the LM head; partials are summed in fixed order by the consumer.
+//     16x16x32: measured 2.2 vs 1.2 PFLOP/s), A staged through LDS once per workgroup and prefetched into
+//     registers ahead of the MFMAs; 4 waves either as a 2 x 2 grid over 128 columns (two row halves x two
+//     64-column groups) or, for single-split grids that are resident all at once, side by side over 256 columns
+//     (no weight fragment is then loaded by two waves).  The weight fragment is the MFMA's first operand, so the
+//     accumulators hold the output transposed (lane = row): every epilogue starts from that.
+//   * split-K over blockIdx.y works in units of 512 k, row passes over blockIdx.z; the split count depends on
+//     (N, K) and the kernel class (M <= 32 or not) only, so the partial-sum grouping of a row never depends on
+//     how many rows travel with it.  Splits fill about half the CUs, two row passes the other half: a split
+//     costs an M x N partial sum written and read again, a row pass only a second read of W from L2.
+//   * output: [split][32-column tile][row][32] fp32 partial sums (summed in fixed order by the consumer), or
+//     row-major logits, or - fused epilogues - bf16 SwiGLU products in the next GEMM's A-fragment layout, or
+//     per-column-group (maximum, column) pairs for the greedy vocabulary reduction.
 // 16x16x32: A lane l = row l%16, k slots 8*(l/16)..+7; B lane l = column l%16, same k slots; D lane l register i
 // = row 4*(l/16)+i, column l%16.   32x32x16: A lane l = row l%32, k slots 8*(l/32)..+7; B lane l = column l%32;
 // D lane l register i = row 8*(i/4) + 4*(l/32) + i%4, column l%32.
@@ -184,9 +189,11 @@ __global__ __launch_bounds__(256) void gemm_bf16_small_kernel(const bf16_t *__re
     store_tiles<MT, NT>(acc, out, blockIdx.y, M, N, tile0, n_tiles, 0, lane, out_row_major);
 }
 
-// ------------------------------------------------------------------ 32 < M: 32x32x16 MFMA, A through LDS, 2 x 2 waves
-// MTA: 32-row tiles per wave; the workgroup pass covers CTL row tiles (2*MTA, or 9 when MTA is 5: the second
-// row half then repeats a tile whose results are dropped).  Chunk of K = 128 (8 k steps); weight ring 16 k steps.
+// ------------------------------------------------------------------ 32 < M: 32x32x16 MFMA, A through LDS
+// MTA: 32-row tiles per wave.  2 x 2 waves (WIDE false): the workgroup pass covers CTL = 2*MTA row tiles (9 when
+// MTA is 5: the second row half then repeats a tile whose results are dropped) of 128 columns.  WIDE: four waves
+// side by side, each over all CTL = MTA row tiles and 64 of the workgroup's 256 columns.  Chunk of K = 128 (8 k
+// steps); weight ring 16 k steps.
 template <int MTA, bool WIDE>
 __global__ __launch_bounds__(256) void gemm_bf16_large_kernel(const bf16_t *__restrict__ a,
                                                               const bf16_t *__restrict__ w, float *__restrict__ out,
