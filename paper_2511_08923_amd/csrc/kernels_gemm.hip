@@ -101,6 +101,25 @@ __device__ inline void store_tiles(const f32x4 (&acc)[MTW][NT], float *out, int 
         }
         return;
     }
+    if (out_row_major == GEMM_EPI_SWIGLU) {
+        // the wave's two 16-column tiles are gate and up of the same 16 features (tile0 is even): a lane holds both
+        // values of (row, feature), so h = silu(gate) * up needs no data movement; it is stored as bf16 in the
+        // A-fragment layout of the next GEMM
+        bf16_t *ho = reinterpret_cast<bf16_t *>(out);
+        const ActLayout lay = act_layout(M);
+        if (tile0 + 1 < n_tiles) {
+#pragma unroll
+            for (int mt = 0; mt < MTW; ++mt)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int row = (mt0 + mt) * 16 + (lane >> 4) * 4 + i;
+                    const float g = acc[mt][0][i], u = acc[mt][1][i];
+                    const float h = g * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-1.4426950408889634f * g)) * u;
+                    if (row < M) ho[af_index(row, (tile0 >> 1) * 16 + (lane & 15), lay)] = (bf16_t)h;
+                }
+        }
+        return;
+    }
     float *o = out + (size_t)split * pt_split_stride(M, N);
 #pragma unroll
     for (int mt = 0; mt < MTW; ++mt) {

@@ -121,7 +121,7 @@ void launch_rmsnorm(int dtype, float *x, const float *part, int S, const void *g
                     int B, int R, int row0, int d_model, void *out, hipStream_t st);
 
 // Epilogue forms of the bf16 GEMM: tiled fp32 partial sums (default), plain row-major fp32 (the logits), or, for the
-// interleaved gate/up matrix with one split and M > 32, SwiGLU applied in registers and h written as bf16 straight
+// interleaved gate/up matrix with one split, SwiGLU applied in registers and h written as bf16 straight
 // into the A-fragment layout of the down projection (out is then a bf16 buffer of af_elems(M, N/2)).
 enum { GEMM_EPI_TILED = 0, GEMM_EPI_ROWMAJOR = 1, GEMM_EPI_SWIGLU = 2, GEMM_EPI_ARGMAX = 3 };
 // GEMM_EPI_ARGMAX (single split): no output matrix; every wave reduces its columns to the largest value of each

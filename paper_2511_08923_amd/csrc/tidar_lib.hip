@@ -257,7 +257,7 @@ void forward_rows(tidar_ctx *ctx, const tidar_weights *w, const tidar_kv_cache *
             launch_rmsnorm(c.dtype, x, gout, S, w->ffn_norm[layer], c.rms_eps, B, d.R, 0, c.d_model, ws + l.xn, st);
         }
         bool fused_swiglu = false;
-        if (c.dtype == TIDAR_BF16 && M > 32) {
+        if (c.dtype == TIDAR_BF16) {
             GemmPlan gp = plan_gemm_bf16(M, 2 * c.d_ff, c.d_model, false);
             if (gp.splits == 1 && gp.m_chunks >= 1) {       // nothing to reduce: SwiGLU can live in the epilogue
                 Prof p(ctx, KC_GEMM, st);
