@@ -168,7 +168,12 @@ tidar_status tidar_prefill(tidar_ctx *ctx, const tidar_weights *w, const tidar_k
  *               unverified position, slots 1..k-1 = argmax of slots 1..k-1 of mask block a-1
  *   logits_out  optional dev fp32 [batch][k(k+1)][vocab], rows in the order
  *               c_0..c_{k-1}, blk_0[0..k), ..., blk_{k-1}[0..k)
- *   max_prefix_len_hint  host upper bound of every prefix_len[b] on entry (capacity check, grid sizing)
+ *   max_prefix_len_hint  host upper bound of every prefix_len[b] on entry (capacity check, grid sizing).
+ *               The attention kernel cuts the key range into equal splits of this bound, so a key's split depends
+ *               on its position and the bound, not on the current length: with one bound held over a run of calls
+ *               (e.g. the length the generation may reach) a row with the same context gets bit-identical logits
+ *               at every step; a bound far above the real length leaves the later splits empty (slower, still
+ *               correct).
  * `drafts` may alias `next_drafts`.
  */
 tidar_status tidar_step(tidar_ctx *ctx, const tidar_weights *w, const tidar_kv_cache *kv, int32_t batch,

@@ -46,7 +46,7 @@ struct AttnArgs {
     const int32_t *prefix_len;
     RowDesc d;
     int n_q, group;
-    int n_chunks, tiles_per_chunk, splits;
+    int n_chunks, tiles_per_chunk, splits, per;
     int inv_bl;                // ceil(65536 / bl)
     int n_pages;               // physical pages per layer (bounds of the page buffers)
     float scale_log2e;
@@ -149,9 +149,13 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
     const int n_mt = (n_mask + 15) >> 4;
     const int U = n_cache_units + n_mt;
     const int n_it = (U + 1) >> 1;
-    const int per = (n_it + a.splits - 1) / a.splits;
-    const int it0 = split * per;
-    const int it1 = min(n_it, it0 + per);
+    // Split s takes key-pair iterations [s*per, (s+1)*per) with per fixed by the host from its bound on the key
+    // count: which split a key falls into does not depend on how long the sequence is right now, so the same
+    // query over the same keys is reduced in the same grouping at every step (the last split takes whatever a
+    // loose bound leaves over; splits past the end write an empty partial).
+    const int per = a.per;
+    const int it0 = min(n_it, split * per);
+    const int it1 = (split == a.splits - 1) ? n_it : min(n_it, it0 + per);
     const int F = a.group * d.R;                     // flattened query rows of this kv head
     const int TQ = (F + 31) >> 5;
     const int t0 = chunk * a.tiles_per_chunk;
@@ -399,6 +403,7 @@ AttnPlan plan_attention(int B, int n_kv, int group, int R, int max_keys) {
         int v = atoi(e);
         if (v >= 1 && v <= 64) p.splits = v < cap ? v : (cap < 1 ? 1 : cap);
     }
+    p.per = (iters + 1 + p.splits - 1) / p.splits;   // +1: the kernel counts cache and scratch units separately
     return p;
 }
 
@@ -421,6 +426,7 @@ void launch_attention_bf16(const bf16_t *q, KvView kv, int n_pages, const bf16_t
     a.n_chunks = p.n_chunks;
     a.tiles_per_chunk = p.tiles_per_chunk;
     a.splits = p.splits;
+    a.per = p.per;
     a.inv_bl = d.bl > 0 ? (65536 + d.bl - 1) / d.bl : 0;
     a.n_pages = n_pages;
     a.scale_log2e = 1.4426950408889634f / sqrtf((float)kv.hd);

@@ -148,6 +148,8 @@ struct AttnPlan {
     int splits;
     int n_chunks;        // q-tile chunks per kv head
     int tiles_per_chunk;
+    int per;             // key-pair iterations per split, from the caller's bound on the key count (not from the
+                         // sequence's current length): a key's split then depends on its position alone
 };
 AttnPlan plan_attention(int B, int n_kv, int group, int R, int max_keys);
 size_t attn_partial_floats(int B, int n_kv, int group, int R, int hd, int splits);
