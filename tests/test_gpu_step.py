@@ -303,6 +303,41 @@ def test_small_bf16_long_prompt_two_default_passes(T):
     eng.close()
 
 
+def test_bf16_logits_do_not_depend_on_the_acceptance_history(T, small):
+    """With one length bound held over the run, a causal row's logits depend on its context alone, bit for bit: the
+    GEMMs group a row's sums the same way whatever rows travel with it, and the attention splits are cut by key
+    position.  Reference: steps that each accept one token (the row is c_0 at its position).  Then the same
+    positions again as rows c_0..c_{k-1} of ONE step whose drafts are the reference tokens."""
+    eng, _ = small
+    sh = TI.SMALL_GQA
+    k, P = 8, 200
+    hint = P + 4 * k
+    prompt = TI.make_prompt(sh, P, seed=123)
+    first, _ = eng.prefill(prompt, k)
+    drafts = first.clone()
+    ref, toks = {}, {}
+    while int(eng.prefix_len[0]) < P + k:
+        L = int(eng.prefix_len[0])
+        a, acc, nxt, lg = eng.step(drafts, k, hint=hint, want_logits=True)
+        torch.cuda.synchronize()
+        ref[L] = lg[0, 0].clone()                   # row c_0: context = everything up to position L
+        for i in range(int(a[0])):
+            toks[L + i] = int(acc[0, i])
+        drafts = nxt.clone()
+    assert all(P + i in toks for i in range(k))
+    eng.prefix_len[:1].fill_(P)                       # same cache contents below P; everything above is rewritten
+    forced = torch.tensor([[toks[P + i] for i in range(k)]], dtype=torch.int32, device="cuda")
+    a, acc, nxt, lg = eng.step(forced, k, hint=hint, want_logits=True)
+    torch.cuda.synchronize()
+    compared = 0
+    for i in range(k):
+        if P + i in ref:
+            assert torch.equal(lg[0, i], ref[P + i]), (i, float((lg[0, i] - ref[P + i]).abs().max()))
+            compared += 1
+    assert compared >= k // 2
+    assert int(a[0]) == k                             # every draft was the reference token: all accepted
+
+
 def test_small_bf16_device_tidar_vs_device_ar(T, small):
     """On-device check 3 in bf16: streams agree until a row whose top-2 margin is within rounding."""
     eng, model = small
