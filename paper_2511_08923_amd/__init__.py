@@ -333,15 +333,16 @@ class Engine:
 
     # -- calls
     def prefill(self, prompt: torch.Tensor, k: int, mode: Optional[tidar_mode] = None,
-                want_logits: bool = False):
+                want_logits: bool = False, prompt_len: Optional[List[int]] = None):
+        """prompt: [batch, max_len] token ids; prompt_len: per-sequence lengths (default: all max_len)."""
         mode = mode or make_mode()
         batch, P = prompt.shape
         prompt_d = prompt.to(self.device, torch.int32).contiguous()
         first = torch.empty(batch, k, dtype=torch.int32, device=self.device)
         logits = (torch.empty(batch, 1 + k, self.shape.vocab, dtype=torch.float32, device=self.device)
                   if want_logits else None)
-        tidar_prefill(self.ctx, self.w, self.kv, batch, prompt_d, [P] * batch, k, mode, self.prefix_len, first, logits,
-                      self.ws)
+        tidar_prefill(self.ctx, self.w, self.kv, batch, prompt_d, list(prompt_len) if prompt_len else [P] * batch, k,
+                      mode, self.prefix_len, first, logits, self.ws)
         return first, logits
 
     def step(self, drafts: torch.Tensor, k: int, hint: int, mode: Optional[tidar_mode] = None,

@@ -105,6 +105,32 @@ def test_tiny_fp32_forced_drafts_and_batch(T, tiny):
         assert eng.prefix_len.tolist() == [40 + pos[0], 40 + pos[1]]
 
 
+def test_tiny_fp32_ragged_prompts_down_to_one_token(T, tiny):
+    """Two sequences with prompts of 1 and 37 tokens in one prefill call (the shorter padded), then greedy TiDAR steps
+    with the device's own drafts: each stream equals the oracle's plain AR decode, token for token."""
+    eng, model = tiny
+    k, n = 4, 12
+    lens = [1, 37]
+    prompts = torch.zeros(2, 37, dtype=torch.int32)
+    for b, P in enumerate(lens):
+        prompts[b, :P] = TI.make_prompt(TI.TINY, P, seed=70 + b)[0]
+    want = [model.ar_decode([int(t) for t in prompts[b, :lens[b]]], n + 2 * k) for b in range(2)]
+    drafts, _ = eng.prefill(prompts, k, prompt_len=lens)
+    torch.cuda.synchronize()
+    assert eng.prefix_len[:2].tolist() == lens
+    got = [[], []]
+    for step in range(n):
+        L = eng.prefix_len[:2].tolist()
+        a, acc, nxt, _ = eng.step(drafts, k, hint=max(L))
+        torch.cuda.synchronize()
+        for b in range(2):
+            got[b] += acc[b, :int(a[b])].tolist()
+        drafts = nxt.clone()
+    for b in range(2):
+        assert len(got[b]) >= n
+        assert got[b] == want[b][:len(got[b])], b
+
+
 def test_tiny_fp32_sampling_matches_oracle(T, tiny):
     eng, model = tiny
     k, n = 4, 24
