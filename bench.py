@@ -509,7 +509,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "launch": "host launches" if args.no_graph else "HIP graph replay of the captured step",
         "config": {"workload": f"{shape.name} TiDAR decode, batch 1, k={k} ({R} rows/step), prompt {P} random tokens, "
-                               f"greedy, acceptance lengths seeded with mean {args.mean_accept} (paper Table 2, 8B)",
+                               f"greedy, acceptance lengths seeded with mean {args.mean_accept} (paper Table 2)",
                    "k": k, "prefix_len": P, "batch": 1, "layers": shape.n_layers},
         "tidar_step_ms": step_ms, "tidar_step_ms_percentiles": step_pcts, "ar_step_ms": ar_ms, "tidar_over_ar_latency": step_ms / ar_ms,
         "ar_tokens_per_s": 1e3 / ar_ms, "tokens_per_step": tokens / args.steps,
