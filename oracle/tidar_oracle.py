@@ -21,6 +21,13 @@ What the paper fixes, and where:
     evicted, nothing is ever recomputed ........................... Section 3.3
   * prefill: prompt causal plus one bidirectional block of masks .. Section 3.2
     and Appendix B
+  * the training-time layout: the text followed by as many mask tokens, the
+    text attended causally, every block of masks bidirectionally together with
+    the text before the block; causal labels shifted by one, mask labels in
+    place; the two cross-entropy sums and their weighting
+    ....................... Section 3.1 (objective), Figure 3 (left) caption
+  * likelihood of a text = the causal section alone, as for any AR model
+    ............................................................ Section 4.2.2
 
 Readings taken where the paper is silent (figures are not available):
   A. the first causal token c_1 is already final (it is the token sampled from
@@ -34,6 +41,12 @@ Readings taken where the paper is silent (figures are not available):
   E. beta = 1 (verify with the causal logits) unless a mix is requested.
   F. argmax ties go to the lowest token id.
   J. RMSNorm eps 1e-6, RoPE pairs dimension i with i + head_dim/2, no biases.
+  N. the objective's two sums are printed with the same index range
+     i = 1..S-1: the causal sum pairs x_i with its successor (S-1 targets,
+     x_2..x_S); the mask sum is read literally as the tokens x_1..x_{S-1}
+     (the last position is left out, both sums have S-1 terms).  The per-token
+     log-probabilities are returned for all S mask positions, so another
+     reading is one slice away.
   K. bf16-faithful mode rounds to bf16 at: normalised activations entering a
      GEMM, Q and K after RoPE, V, softmax numerators, attention output, the
      SwiGLU product; weights are bf16 values; the residual stream and all
@@ -131,6 +144,46 @@ def causal_mask(n_new: int, L: int) -> torch.Tensor:
     for t in range(n_new):
         M[t, : L + t + 1] = True
     return M
+
+
+# --------------------------------------------------------------------------
+# Training-time layout (Section 3.1, Figure 3 left caption): rows and columns
+# are the S text tokens followed by S mask tokens; mask i stands in for token i
+# and belongs to block i // bl (the last block is short when bl does not
+# divide S).
+# --------------------------------------------------------------------------
+
+
+def training_mask(S: int, bl: int) -> torch.Tensor:
+    """Boolean [2S, 2S] attend-matrix of the doubled training sequence."""
+    M = torch.zeros(2 * S, 2 * S, dtype=torch.bool)
+    for t in range(S):                                  # text: causal, never sees a mask
+        M[t, : t + 1] = True
+    for i in range(S):
+        j = i // bl
+        M[S + i, : j * bl] = True                       # the text before its block
+        for ip in range(j * bl, min((j + 1) * bl, S)):  # its own block, both directions
+            M[S + i, S + ip] = True
+    return M
+
+
+def training_positions(S: int) -> torch.Tensor:
+    """A mask keeps the position of the token it stands in for (labels are not shifted, Section 3.1)."""
+    return torch.cat([torch.arange(S, dtype=torch.int64), torch.arange(S, dtype=torch.int64)])
+
+
+def tidar_loss(ar_logprob: torch.Tensor, diff_logprob: torch.Tensor, alpha: float) -> float:
+    """Section 3.1 objective from per-token log-probabilities (reading N).
+
+    ar_logprob [S-1]: log p(x_{i+1} | x_{<=i}) from the causal section; diff_logprob [S]: log p(x_i | text
+    before its block, masks) from the mask section.  Both sums have S-1 terms and are divided by S-1; the
+    causal one is weighted by alpha, the total by 1/(1+alpha).
+    """
+    S = diff_logprob.shape[0]
+    assert ar_logprob.shape[0] == S - 1 and S >= 2
+    l_ar = -float(ar_logprob.sum()) / (S - 1)
+    l_diff = -float(diff_logprob[: S - 1].sum()) / (S - 1)
+    return (alpha * l_ar + l_diff) / (1.0 + alpha)
 
 
 # --------------------------------------------------------------------------
@@ -347,6 +400,29 @@ class OracleModel:
             tok, _ = self.ar_step(state, tok, mode)
             out.append(tok)
         return out
+
+    # ---- likelihood of a text in AR mode (Section 4.2.2) ----
+    def score(self, tokens: Sequence[int]) -> torch.Tensor:
+        """log p(x_{i+1} | x_0..x_i) for i = 0..S-2 under the pure causal mask: [S-1]."""
+        S = len(tokens)
+        state = self.new_state(S)
+        t = torch.tensor(list(tokens), dtype=torch.int64)
+        logits, _, _ = self.forward(t, torch.arange(S, dtype=torch.int64), causal_mask(S, 0), state)
+        lp = torch.log_softmax(logits, dim=-1)
+        return lp[torch.arange(S - 1), t[1:]]
+
+    # ---- one forward over the doubled training sequence (Section 3.1) ----
+    def training_forward(self, tokens: Sequence[int], bl: int) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
+        """Returns (causal log-probs [S-1], label shifted; mask log-probs [S], labels in place; logits [2S, V])."""
+        S = len(tokens)
+        state = self.new_state(1)
+        t = torch.tensor(list(tokens), dtype=torch.int64)
+        rows = torch.cat([t, torch.full((S,), self.shape.mask_token_id, dtype=torch.int64)])
+        logits, _, _ = self.forward(rows, training_positions(S), training_mask(S, bl), state)
+        lp = torch.log_softmax(logits, dim=-1)
+        ar = lp[torch.arange(S - 1), t[1:]]
+        diff = lp[S + torch.arange(S), t]
+        return ar, diff, logits
 
     def tidar_decode(self, prompt: Sequence[int], n_tokens: int, k: int, mode: Mode = Mode(), seq_id: int = 0,
                      draft_override=None) -> Tuple[List[int], List[int]]:
