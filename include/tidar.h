@@ -221,15 +221,36 @@ tidar_status tidar_gemm(tidar_ctx *ctx, const void *a, const void *w_packed, flo
                         int32_t M, int32_t N, int32_t K, void *ws, size_t ws_bytes, void *stream);
 
 /*
- * Per-kernel timing with HIP events on the launch stream.  While enabled,
- * every kernel class the library launches is bracketed by events; reading
- * synchronises the recorded events.  `names`/`ms`/`launches` receive up to
- * `cap` entries; the return value is the number of kernel classes seen.
- * Timing a whole step should be done with profiling off.
+ * Likelihood of a text in AR mode (paper Section 4.2.2: the causal section alone scores a text the way any
+ * autoregressive model does, one forward) and, with block_len > 0, the forward over the doubled training sequence
+ * (Section 3.1, Figure 3 left): the text followed by one mask token per text position, the text attended causally,
+ * the masks of a block (block j covers positions [j*block_len, (j+1)*block_len), the last block may be short)
+ * attending to each other in both directions and to the text before their block; a mask keeps the position id of
+ * the token it stands in for.  Forward only: log-probabilities and the objective's value, no gradients.
+ *   tokens   dev int32 [batch][stride]; len host int32 [batch], 1 <= len[b] <= stride
+ *   block_len 0: causal section only (diff_logprob must be NULL); 1..16: both sections (diff_logprob required)
+ *   ar_logprob   dev fp32 [batch][stride] out: entry i = ln p(tokens[i+1] | tokens[0..i]) from the causal row i
+ *                (labels shifted by one), i < len-1; entry len-1 is set to 0, later entries are untouched
+ *   diff_logprob dev fp32 [batch][stride] out: entry i = ln p(tokens[i] | text before the block of i, masks) from
+ *                the mask row of position i (labels in place), i < len
+ *   loss     optional dev fp32 [batch] out: the Section 3.1 objective of each sequence,
+ *            (alpha * A + D) / (1 + alpha) with A = -mean of ar_logprob[0..len-1) and D = -mean of
+ *            diff_logprob[0..len-1) (both sums printed with len-1 terms: the last mask position takes no part);
+ *            with block_len = 0 it is A; 0 for a one-token text.  alpha in [0, 1].
+ * The sequences are run one after another in passes of the prefill chunk's causal rows (rounded down to whole
+ * blocks) through the step's kernels, every row through the LM head.  The K/V cache pages of sequences
+ * 0..batch-1 are overwritten with the text's K/V (positions [0, len)); the caller's prefix_len array is not
+ * involved.  ws must hold tidar_score_workspace_bytes(max over len, block_len) bytes.
  */
+tidar_status tidar_score_workspace_bytes(const tidar_ctx *ctx, int32_t max_len, int32_t block_len, size_t *bytes);
+tidar_status tidar_score(tidar_ctx *ctx, const tidar_weights *w, const tidar_kv_cache *kv, int32_t batch,
+                         const int32_t *tokens, int32_t stride, const int32_t *len, int32_t block_len, float alpha,
+                         float *ar_logprob, float *diff_logprob, float *loss, void *ws, size_t ws_bytes,
+                         void *stream);
+
 /* Causal rows per prefill pass (the prompt is prefilled in causal chunks through the step's kernels, the mask block
  * of Appendix B joins the last chunk).  Default 1024; 1..4096.  Larger passes stream the weights fewer times and
- * need a larger workspace: call before tidar_workspace_bytes.  Host only. */
+ * need a larger workspace: call before tidar_workspace_bytes / tidar_score_workspace_bytes.  Host only. */
 tidar_status tidar_set_prefill_chunk(tidar_ctx *ctx, int32_t rows);
 
 /* Block length for the coming steps (paper, Limitations, "Batch size": the block length can be changed between
@@ -241,6 +262,13 @@ tidar_status tidar_set_prefill_chunk(tidar_ctx *ctx, int32_t rows);
  * invalid arguments (ctx NULL, batch < 1). */
 int32_t tidar_select_block_len(const tidar_ctx *ctx, int32_t batch, int32_t k_cap, int32_t row_budget);
 
+/*
+ * Per-kernel timing with HIP events on the launch stream.  While enabled,
+ * every kernel class the library launches is bracketed by events; reading
+ * synchronises the recorded events.  `names`/`ms`/`launches` receive up to
+ * `cap` entries; the return value is the number of kernel classes seen.
+ * Timing a whole step should be done with profiling off.
+ */
 tidar_status tidar_profile_enable(tidar_ctx *ctx, int32_t on);
 int32_t      tidar_profile_read(tidar_ctx *ctx, const char **names, double *ms, int64_t *launches, int32_t cap);
 tidar_status tidar_profile_reset(tidar_ctx *ctx);

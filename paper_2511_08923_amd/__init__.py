@@ -27,7 +27,8 @@ STATUS = {0: "TIDAR_OK", 1: "TIDAR_EINVAL", 2: "TIDAR_ENOMEM", 3: "TIDAR_ECAPACI
 EXPORTS = ["tidar_create", "tidar_destroy", "tidar_strerror", "tidar_packed_weight_bytes", "tidar_pack_weight",
            "tidar_workspace_bytes", "tidar_prefill", "tidar_step", "tidar_ar_step", "tidar_hybrid_attention",
            "tidar_gemm_workspace_bytes", "tidar_gemm", "tidar_profile_enable", "tidar_profile_read",
-           "tidar_profile_reset", "tidar_select_block_len", "tidar_set_prefill_chunk"]
+           "tidar_profile_reset", "tidar_select_block_len", "tidar_set_prefill_chunk", "tidar_score_workspace_bytes",
+           "tidar_score"]
 
 
 class TidarError(RuntimeError):
@@ -101,6 +102,11 @@ def _load() -> C.CDLL:
     lib.tidar_select_block_len.restype = i32
     lib.tidar_set_prefill_chunk.argtypes = [vp, i32]
     lib.tidar_set_prefill_chunk.restype = i32
+    lib.tidar_score_workspace_bytes.argtypes = [vp, i32, i32, C.POINTER(sz)]
+    lib.tidar_score_workspace_bytes.restype = i32
+    lib.tidar_score.argtypes = [vp, C.POINTER(tidar_weights), C.POINTER(tidar_kv_cache), i32, vp, i32, C.POINTER(i32),
+                                i32, C.c_float, vp, vp, vp, vp, sz, vp]
+    lib.tidar_score.restype = i32
     return lib
 
 
@@ -208,6 +214,21 @@ def tidar_set_prefill_chunk(ctx, rows: int) -> None:
 
 def tidar_select_block_len(ctx, batch: int, k_cap: int = 0, row_budget: int = 0) -> int:
     return int(_lib.tidar_select_block_len(ctx, batch, k_cap, row_budget))
+
+
+def tidar_score_workspace_bytes(ctx, max_len: int, block_len: int) -> int:
+    n = C.c_size_t()
+    _check(_lib.tidar_score_workspace_bytes(ctx, max_len, block_len, C.byref(n)), "tidar_score_workspace_bytes")
+    return int(n.value)
+
+
+def tidar_score(ctx, w: tidar_weights, kv: tidar_kv_cache, batch: int, tokens: torch.Tensor, length: Sequence[int],
+                block_len: int, alpha: float, ar_logprob: torch.Tensor, diff_logprob: Optional[torch.Tensor],
+                loss: Optional[torch.Tensor], ws: torch.Tensor) -> None:
+    lens = (C.c_int32 * batch)(*[int(x) for x in length])
+    _check(_lib.tidar_score(ctx, C.byref(w), C.byref(kv), batch, tokens.data_ptr(), tokens.shape[1], lens, block_len,
+                            alpha, ar_logprob.data_ptr(), _ptr(diff_logprob), _ptr(loss), ws.data_ptr(),
+                            ws.numel() * ws.element_size(), _stream()), "tidar_score")
 
 
 def tidar_profile_reset(ctx) -> None:
@@ -370,6 +391,20 @@ class Engine:
                   if want_logits else None)
         tidar_ar_step(self.ctx, self.w, self.kv, batch, self.prefix_len, token_in, mode, out, logits, hint, self.ws)
         return out, logits
+
+    def score(self, tokens: torch.Tensor, block_len: int = 0, alpha: float = 1.0,
+              length: Optional[List[int]] = None):
+        """tokens: [batch, max_len].  Returns (ar_logprob, diff_logprob or None, loss), device tensors."""
+        batch, S = tokens.shape
+        tok_d = tokens.to(self.device, torch.int32).contiguous()
+        lens = list(length) if length else [S] * batch
+        need = tidar_score_workspace_bytes(self.ctx, max(lens), block_len)
+        ws = self.ws if need <= self.ws_bytes else torch.empty(need, dtype=torch.uint8, device=self.device)
+        ar = torch.zeros(batch, S, dtype=torch.float32, device=self.device)
+        diff = torch.zeros(batch, S, dtype=torch.float32, device=self.device) if block_len > 0 else None
+        loss = torch.zeros(batch, dtype=torch.float32, device=self.device)
+        tidar_score(self.ctx, self.w, self.kv, batch, tok_d, lens, block_len, alpha, ar, diff, loss, ws)
+        return ar, diff, loss
 
     # -- cache views for tests: gather K ([L, n_kv, hd]) and V of one sequence and layer out of the pages
     def read_cache(self, layer: int, seq: int, length: int):

@@ -143,7 +143,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
     const int split = blockIdx.y;
     const RowDesc d = a.d;
     const int L = a.prefix_len[d.seq_base + b];
-    const int n_mask = d.nb * d.bl;
+    const int n_mask = d.nm;
     const int n_cache_units = (L + d.nc + 15) >> 4;
     const int n_pure = L >> 4;
     const int n_mt = (n_mask + 15) >> 4;

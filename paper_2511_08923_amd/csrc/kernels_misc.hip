@@ -196,7 +196,7 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(const float *__restrict__ 
     const bool causal = r < d.nc;
     const int L = prefix_len[d.seq_base + b];
     int page = 0, slot = 0, mt = 0;
-    const int n_mtiles = (d.nb * d.bl + 15) / 16;
+    const int n_mtiles = (d.nm + 15) / 16;
     if (causal) {
         int p = L + r;
         page = kv.page_table[(size_t)(d.seq_base + b) * kv.pages_per_seq + (p >> 4)];
@@ -246,7 +246,7 @@ __global__ void place_kv_kernel(const T *__restrict__ k_new, const T *__restrict
     bool causal = r < d.nc;
     int L = prefix_len[d.seq_base + b];
     int page = 0, slot = 0, mt = 0;
-    int n_mtiles = (d.nb * d.bl + 15) / 16;
+    int n_mtiles = (d.nm + 15) / 16;
     if (causal) {
         int p = L + r;
         page = kv.page_table[(size_t)(d.seq_base + b) * kv.pages_per_seq + (p >> 4)];
@@ -355,6 +355,83 @@ __global__ void argmax_rows_kernel(const float *__restrict__ logits, int Rh, int
         for (int w = 1; w < (int)(blockDim.x >> 6); ++w)
             if (sb[w] > best || (sb[w] == best && si[w] < best_i)) { best = sb[w]; best_i = si[w]; }
         y[row] = best_i;
+    }
+}
+
+// ------------------------------------------------------------------ log-probability of a label under a row of logits
+// One block per row of one scoring pass over text positions [c0, c0 + nc) of a sequence of `len` tokens.  Causal row
+// r is label shifted (Section 3.1): it scores token c0 + r + 1 into ar_out[c0 + r] (0 when the text ends there);
+// mask row m is scored against the token it stands in for, c0 + m, into diff_out[c0 + m].
+// log p = logit[label] - (max + ln sum exp(logit - max)), two passes over the row.
+__global__ __launch_bounds__(1024) void score_rows_kernel(const float *__restrict__ logits, int vocab,
+                                                         const int32_t *__restrict__ text, int len, int c0, int nc,
+                                                         float *__restrict__ ar_out, float *__restrict__ diff_out) {
+    const int r = blockIdx.x;
+    const float *lg = logits + (size_t)r * vocab;
+    const bool causal = r < nc;
+    const int i = c0 + (causal ? r : r - nc);
+    const int li = causal ? i + 1 : i;
+    float *dst = (causal ? ar_out : diff_out) + i;
+    if (li >= len) {                       // uniform over the block
+        if (threadIdx.x == 0) *dst = 0.f;
+        return;
+    }
+    const int label = text[li];
+    __shared__ float red[16];
+    __shared__ float bc;
+    const int nw = blockDim.x >> 6;
+    float mx = -INFINITY;
+    for (int v = 4 * threadIdx.x; v < vocab; v += 4 * blockDim.x) {        // vocab is a multiple of 16
+        const float4 q = *(const float4 *)(lg + v);
+        mx = fmaxf(fmaxf(mx, fmaxf(q.x, q.y)), fmaxf(q.z, q.w));
+    }
+    mx = wave_max(mx);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mx;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float m = red[0];
+        for (int w = 1; w < nw; ++w) m = fmaxf(m, red[w]);
+        bc = m;
+    }
+    __syncthreads();
+    mx = bc;
+    float sum = 0.f;
+    for (int v = 4 * threadIdx.x; v < vocab; v += 4 * blockDim.x) {
+        const float4 q = *(const float4 *)(lg + v);
+        sum += (expf(q.x - mx) + expf(q.y - mx)) + (expf(q.z - mx) + expf(q.w - mx));
+    }
+    sum = wave_sum(sum);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = sum;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float t = 0.f;
+        for (int w = 0; w < nw; ++w) t += red[w];
+        *dst = lg[label] - (mx + logf(t));
+    }
+}
+
+// Section 3.1 objective of one sequence from its per-token log-probabilities: both sums run over the first len-1
+// entries and are divided by len-1; the causal one is weighted by alpha, the total by 1/(1+alpha).  Without a mask
+// section (diff == nullptr) the result is the plain mean negative log-likelihood.  One block, fixed summation order;
+// n = len - 1.
+__global__ __launch_bounds__(256) void score_loss_kernel(const float *__restrict__ ar, const float *__restrict__ diff,
+                                                        int n, float alpha, float *__restrict__ loss) {
+    float sa = 0.f, sd = 0.f;
+    for (int i = threadIdx.x; i < n; i += blockDim.x) {
+        sa += ar[i];
+        if (diff) sd += diff[i];
+    }
+    sa = wave_sum(sa);
+    sd = wave_sum(sd);
+    __shared__ float ra[4], rd[4];
+    if ((threadIdx.x & 63) == 0) { ra[threadIdx.x >> 6] = sa; rd[threadIdx.x >> 6] = sd; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const float ta = ((ra[0] + ra[1]) + ra[2]) + ra[3], td = ((rd[0] + rd[1]) + rd[2]) + rd[3];
+        float v = 0.f;
+        if (n > 0) v = diff ? (alpha * (-ta / n) + (-td / n)) / (1.f + alpha) : -ta / n;
+        *loss = v;
     }
 }
 
@@ -521,7 +598,7 @@ __global__ __launch_bounds__(64) void attention_f32_kernel(const float *__restri
     int g = head / (n_q / n_kv);
     int L = prefix_len[d.seq_base + b];
     RowInfo ri = row_info(d, r, L);
-    int n_cache = L + d.nc, n_mask = d.nb * d.bl, n_mtiles = (n_mask + 15) / 16;
+    int n_cache = L + d.nc, n_mask = d.nm, n_mtiles = (n_mask + 15) / 16;
     int T = n_cache + n_mask;
     const float *kp = (const float *)kv.k_pages;
     const float *vp = (const float *)kv.v_pages;
@@ -716,6 +793,15 @@ void launch_argmax_rows(const float *logits, int B, int Rh, int vocab, int n_cho
                         float beta, int mix_base, int mix_stride, int32_t *y, hipStream_t st) {
     argmax_rows_kernel<<<B * Rh, 1024, 0, st>>>(logits, Rh, vocab, n_choose, pos_rows, pos_stride, pos_row0, seq_base,
                                                 sample, temperature, seed, beta, mix_base, mix_stride, y);
+}
+
+void launch_score_rows(const float *logits, int rows, int vocab, const int32_t *text, int len, int c0, int nc,
+                       float *ar_out, float *diff_out, hipStream_t st) {
+    score_rows_kernel<<<rows, 1024, 0, st>>>(logits, vocab, text, len, c0, nc, ar_out, diff_out);
+}
+
+void launch_score_loss(const float *ar, const float *diff, int n, float alpha, float *loss, hipStream_t st) {
+    score_loss_kernel<<<1, 256, 0, st>>>(ar, diff, n, alpha, loss);
 }
 
 void launch_verify_step(const int32_t *y, const int32_t *drafts, int k, int B, int32_t *prefix_len,

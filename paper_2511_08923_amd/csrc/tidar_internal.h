@@ -12,11 +12,15 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 // Row structure of one forward, identical for every sequence of the batch.
-// Rows per sequence: nc causal rows, then nb blocks of bl mask rows.
-// Block j is conditioned on the first cond0 + j causal rows.
+// Rows per sequence: nc causal rows, then nm mask rows in nb blocks of bl (the last block may be short).
+// Block j is conditioned on the first cond0 + j * cstride causal rows and sits at the positions right after
+// them: cstride 1 is the decode step (one block per possible acceptance length), cstride bl the training layout
+// (block j stands in for causal rows [j*bl, (j+1)*bl), Section 3.1).
 struct RowDesc {
     int nc, nb, bl, cond0;
-    int R;          // nc + nb * bl
+    int cstride;
+    int nm;         // mask rows: (nb - 1) * bl < nm <= nb * bl
+    int R;          // nc + nm
     int seq_base;   // first sequence index (into prefix_len / page_table rows)
 };
 
@@ -36,8 +40,8 @@ __host__ __device__ inline RowInfo row_info(const RowDesc &d, int r, int L) {
         int m = r - d.nc;
         int j = m / d.bl;
         int s = m - j * d.bl;
-        ri.pos = L + d.cond0 + j + s;
-        ri.vis = d.cond0 + j;
+        ri.vis = d.cond0 + j * d.cstride;
+        ri.pos = L + ri.vis + s;
         ri.blk = j;
     }
     return ri;
@@ -93,7 +97,7 @@ __device__ inline size_t v_page_offset(const KvView &kv, int page, int h, int sl
 // Profiling hooks (defined in tidar_lib.hip).
 enum KernelClass {
     KC_EMBED = 0, KC_RMSNORM, KC_GEMM, KC_ROPE_KV, KC_ATTN, KC_ATTN_COMBINE, KC_SWIGLU, KC_ARGMAX, KC_VERIFY,
-    KC_PACK, KC_PLACE_KV, KC_COUNT
+    KC_PACK, KC_PLACE_KV, KC_SCORE, KC_COUNT
 };
 
 struct GemmPlan {
@@ -170,6 +174,13 @@ void launch_swiglu(int dtype, const float *part, int S, int M, int d_ff, void *o
 void launch_argmax_rows(const float *logits, int B, int Rh, int vocab, int n_choose, const int32_t *pos_rows,
                         int pos_stride, int pos_row0, int seq_base, int sample, float temperature, uint64_t seed,
                         float beta, int mix_base, int mix_stride, int32_t *y, hipStream_t st);
+
+// Scoring (Section 3.1, Section 4.2.2): log-probability of each row's label under row-major logits of one pass over
+// text positions [c0, c0 + nc) (nc causal rows, then the mask rows), and the objective of one sequence from its
+// first n = len - 1 entries.
+void launch_score_rows(const float *logits, int rows, int vocab, const int32_t *text, int len, int c0, int nc,
+                       float *ar_out, float *diff_out, hipStream_t st);
+void launch_score_loss(const float *ar, const float *diff, int n, float alpha, float *loss, hipStream_t st);
 
 void launch_verify_step(const int32_t *y, const int32_t *drafts, int k, int B, int32_t *prefix_len,
                         int32_t *accepted_len, int32_t *accepted_tokens, int32_t *next_drafts, hipStream_t st);

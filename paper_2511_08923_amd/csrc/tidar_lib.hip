@@ -12,7 +12,8 @@
 namespace {
 
 const char *kClassNames[KC_COUNT] = {"embed_rows", "rmsnorm", "gemm", "rope_kv", "attention", "attention_combine",
-                                     "swiglu", "argmax_rows", "verify", "pack_weight", "place_kv"};
+                                     "swiglu", "argmax_rows", "verify", "pack_weight", "place_kv",
+                                     "score_rows"};
 
 struct ProfEvent {
     int cls;
@@ -218,13 +219,20 @@ void attention(tidar_ctx *ctx, const Layout &l, char *ws, KvView kvv, int n_page
     }
 }
 
+// What a scoring pass does with its logits instead of choosing tokens: rows cover text positions [c0, c0 + nc).
+struct ScorePass {
+    const int32_t *text;   // device, the sequence's tokens
+    int len, c0;
+    float *ar_out, *diff_out;
+};
+
 // One forward over B sequences with row structure d.  head_row0 < 0: no LM head.  Otherwise rows
 // [head_row0, R) of every sequence go through the final norm, the LM head and the vocabulary reduction;
 // the chosen tokens land in ws + layout.y.
 void forward_rows(tidar_ctx *ctx, const tidar_weights *w, const tidar_kv_cache *kv, int B, RowDesc d,
                   const int32_t *tokens, int tok_stride, const int32_t *prefix_len, int max_keys, int head_row0,
                   int n_choose, const tidar_mode *mode, int mix_base, int mix_stride, float *logits_dst,
-                  const Layout &l, char *ws, hipStream_t st) {
+                  const Layout &l, char *ws, hipStream_t st, const ScorePass *score = nullptr) {
     const tidar_config &c = ctx->cfg;
     const int M = B * d.R;
     const int q_dim = c.n_q_heads * c.head_dim, kv_dim = c.n_kv_heads * c.head_dim;
@@ -282,6 +290,14 @@ void forward_rows(tidar_ctx *ctx, const tidar_weights *w, const tidar_kv_cache *
         launch_rmsnorm(c.dtype, x, gout, S_prev, w->final_norm, c.rms_eps, B, d.R, head_row0, c.d_model, ws + l.xh, st);
     }
     float *logits = logits_dst ? logits_dst : (float *)(ws + l.logits);
+    if (score) {               // one sequence; every row's label is scored, no token is chosen
+        int S1 = 1;
+        gemm(ctx, ws + l.xh, w->lm_head, logits, Mh, c.vocab, c.d_model, true, &S1, st);
+        Prof p(ctx, KC_SCORE, st);
+        launch_score_rows(logits, Mh, c.vocab, score->text, score->len, score->c0, d.nc, score->ar_out,
+                          score->diff_out, st);
+        return;
+    }
     // Greedy, AR-trusting, nobody asked for the logits: every row's answer is a plain argmax, which the LM head's
     // epilogue forms per column group; the logits are never written.  (Its partial results fit the logits area:
     // 8 bytes per row and 32 or 64 columns.)
@@ -313,6 +329,8 @@ RowDesc step_desc(int k) {
     d.nb = k;
     d.bl = k;
     d.cond0 = 1;
+    d.cstride = 1;
+    d.nm = k * k;
     d.R = k * (k + 1);
     d.seq_base = 0;
     return d;
@@ -323,6 +341,8 @@ RowDesc ar_desc() {
     d.nb = 0;
     d.bl = 1;
     d.cond0 = 1;
+    d.cstride = 1;
+    d.nm = 0;
     d.R = 1;
     d.seq_base = 0;
     return d;
@@ -333,10 +353,38 @@ RowDesc prefill_desc(int nc, int k, bool last, int seq) {
     d.nb = last ? 1 : 0;
     d.bl = k;
     d.cond0 = nc;
+    d.cstride = 1;
+    d.nm = last ? k : 0;
     d.R = nc + (last ? k : 0);
     d.seq_base = seq;
     return d;
 }
+
+// Scoring pass over text positions [c0, c0 + nc): the causal rows, and with block_len > 0 one mask row per
+// position, in blocks that start at multiples of block_len (c0 is one) and see the text before them.
+RowDesc score_desc(int nc, int block_len, int seq) {
+    RowDesc d;
+    d.nc = nc;
+    d.bl = block_len > 0 ? block_len : 1;
+    d.nb = block_len > 0 ? (nc + block_len - 1) / block_len : 0;
+    d.cond0 = 0;
+    d.cstride = d.bl;
+    d.nm = block_len > 0 ? nc : 0;
+    d.R = nc + d.nm;
+    d.seq_base = seq;
+    return d;
+}
+
+int score_chunk(const tidar_ctx *ctx, int block_len) {
+    int chunk = ctx->prefill_chunk;
+    if (block_len > 0) {
+        chunk -= chunk % block_len;
+        if (chunk < block_len) chunk = block_len;
+    }
+    return chunk;
+}
+
+size_t score_header_bytes(const tidar_config &c) { return align_up((size_t)c.max_batch * 4); }
 
 }  // namespace
 
@@ -524,6 +572,73 @@ tidar_status tidar_prefill(tidar_ctx *ctx, const tidar_weights *w, const tidar_k
     return TIDAR_OK;
 }
 
+tidar_status tidar_score_workspace_bytes(const tidar_ctx *ctx, int32_t max_len, int32_t block_len, size_t *bytes) {
+    if (!ctx || !bytes || max_len < 1 || block_len < 0 || block_len > TIDAR_MAX_K) return TIDAR_EINVAL;
+    const tidar_config &c = ctx->cfg;
+    const int chunk = score_chunk(ctx, block_len);
+    size_t t = 0;
+    // the workspace grows with the key bound for a given pass shape, and no pass ends beyond max_len
+    for (int nc = 1; nc <= chunk && nc <= max_len; ++nc) {
+        RowDesc d = score_desc(nc, block_len, 0);
+        Layout l = make_layout(c, 1, d.R, d.nm, d.R, max_len + d.nm, true);
+        if (l.total > t) t = l.total;
+    }
+    *bytes = score_header_bytes(c) + t;
+    return TIDAR_OK;
+}
+
+tidar_status tidar_score(tidar_ctx *ctx, const tidar_weights *w, const tidar_kv_cache *kv, int32_t batch,
+                         const int32_t *tokens, int32_t stride, const int32_t *len, int32_t block_len, float alpha,
+                         float *ar_logprob, float *diff_logprob, float *loss, void *ws, size_t ws_bytes,
+                         void *stream) {
+    if (!ctx || !weights_ok(w) || !kv_ok(kv) || !tokens || !len || !ar_logprob || !ws) return TIDAR_EINVAL;
+    const tidar_config &c = ctx->cfg;
+    if (batch < 1 || batch > c.max_batch || stride < 1 || block_len < 0 || block_len > TIDAR_MAX_K)
+        return TIDAR_EINVAL;
+    if ((block_len > 0) != (diff_logprob != nullptr)) return TIDAR_EINVAL;
+    if (!(alpha >= 0.f && alpha <= 1.f)) return TIDAR_EINVAL;
+    const int chunk = score_chunk(ctx, block_len);
+    const size_t hdr = score_header_bytes(c);
+    for (int b = 0; b < batch; ++b) {      // size every pass before anything is enqueued
+        if (len[b] < 1 || len[b] > stride) return TIDAR_EINVAL;
+        if ((int64_t)len[b] > (int64_t)kv->pages_per_seq * TIDAR_PAGE_SIZE) return TIDAR_ECAPACITY;
+        for (int c0 = 0; c0 < len[b]; c0 += chunk) {
+            RowDesc d = score_desc(len[b] - c0 < chunk ? len[b] - c0 : chunk, block_len, b);
+            Layout l = make_layout(c, 1, d.R, d.nm, d.R, c0 + d.R, true);
+            if (hdr + l.total > ws_bytes) return TIDAR_ENOMEM;
+        }
+    }
+    hipStream_t st = (hipStream_t)stream;
+    int32_t *cur = (int32_t *)ws;          // the passes' own prefix lengths, one entry per sequence
+    char *wsb = (char *)ws + hdr;
+    tidar_mode gm;
+    gm.sample = 0;
+    gm.temperature = 1.f;
+    gm.seed = 0;
+    gm.beta = 1.f;
+    for (int b = 0; b < batch; ++b) {
+        const int32_t *text = tokens + (size_t)b * stride;
+        for (int c0 = 0; c0 < len[b]; c0 += chunk) {
+            RowDesc d = score_desc(len[b] - c0 < chunk ? len[b] - c0 : chunk, block_len, b);
+            Layout l = make_layout(c, 1, d.R, d.nm, d.R, c0 + d.R, true);
+            launch_set_i32(cur + b, 1, c0, st);
+            ScorePass sp;
+            sp.text = text;
+            sp.len = len[b];
+            sp.c0 = c0;
+            sp.ar_out = ar_logprob + (size_t)b * stride;
+            sp.diff_out = diff_logprob ? diff_logprob + (size_t)b * stride : nullptr;
+            forward_rows(ctx, w, kv, 1, d, text + c0, stride, cur, c0 + d.R, 0, 0, &gm, 0, 0, nullptr, l, wsb, st, &sp);
+        }
+        if (loss) {
+            Prof p(ctx, KC_SCORE, st);
+            launch_score_loss(ar_logprob + (size_t)b * stride, diff_logprob ? diff_logprob + (size_t)b * stride : nullptr,
+                              len[b] - 1, alpha, loss + b, st);
+        }
+    }
+    return TIDAR_OK;
+}
+
 tidar_status tidar_hybrid_attention(tidar_ctx *ctx, const tidar_kv_cache *kv, int32_t layer, int32_t batch,
                                     const int32_t *prefix_len, const void *q, const void *k_new, const void *v_new,
                                     int32_t n_causal, int32_t n_blocks, int32_t block_len, int32_t cond0, void *out,
@@ -542,6 +657,8 @@ tidar_status tidar_hybrid_attention(tidar_ctx *ctx, const tidar_kv_cache *kv, in
     d.nb = n_blocks;
     d.bl = block_len;
     d.cond0 = cond0;
+    d.cstride = 1;
+    d.nm = n_blocks * block_len;
     d.R = n_causal + n_blocks * block_len;
     d.seq_base = 0;
     size_t es = esize(c.dtype);
