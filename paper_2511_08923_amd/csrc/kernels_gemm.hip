@@ -216,9 +216,26 @@ __global__ __launch_bounds__(256) void gemm_bf16_small_kernel(const bf16_t *__re
 template <int MTA, bool WIDE>
 __global__ __launch_bounds__(256) void gemm_bf16_large_kernel(const bf16_t *__restrict__ a,
                                                               const bf16_t *__restrict__ w, float *__restrict__ out,
-                                                              int M, int N, int K, int splits, int epi) {
-    constexpr int NT = 2, KS = 8, PFK = 16;
+                                                              int M, int N, int K, int splits, int epi,
+                                                              int swz_p, int swz_c, int n_pass, int n_colblk) {
+    constexpr int NT = 2, KS = 8;
+    constexpr int PFK = MTA >= 8 ? KS : 2 * KS;  // weight ring depth in k steps: one chunk or two
     constexpr int CTL = WIDE ? MTA : (MTA == 5) ? 9 : 2 * MTA;
+    // Many row passes: the (pass, column block) plane is cut into super-tiles of swz_p x swz_c workgroups, each
+    // handed whole to one XCD (workgroup i of a launch runs on XCD i % 8), passes fastest: the workgroups that
+    // are resident together on an XCD then share their A rows and W columns through its L2 instead of each
+    // streaming a private W slice from HBM.
+    int bx = blockIdx.x, bz = blockIdx.z;
+    if (swz_p > 0) {
+        const int i = blockIdx.x, xcd = i & 7, j = i >> 3;
+        const int per = swz_p * swz_c;
+        const int n_sp = (n_pass + swz_p - 1) / swz_p, n_sc = (n_colblk + swz_c - 1) / swz_c;
+        const int st = (j / per) * 8 + xcd, within = j % per;
+        if (st >= n_sp * n_sc) return;
+        bz = (st % n_sp) * swz_p + within % swz_p;
+        bx = (st / n_sp) * swz_c + within / swz_p;
+        if (bz >= n_pass || bx >= n_colblk) return;
+    }
     constexpr int PIECES = CTL * KS * 64;        // 16-byte pieces per chunk
     constexpr int STAGE = (PIECES + 255) / 256;
     constexpr int FR = KS * MTA;                 // A fragments a wave consumes per chunk
@@ -230,13 +247,13 @@ __global__ __launch_bounds__(256) void gemm_bf16_large_kernel(const bf16_t *__re
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int mh = WIDE ? 0 : wave & 1, ng = WIDE ? wave : wave >> 1;
     const int t32 = (N + 31) >> 5, m_tiles = (M + 31) >> 5;
-    const int mt_base = blockIdx.z * CTL;
+    const int mt_base = bz * CTL;
     const int ct_here = min(CTL, m_tiles - mt_base);
     const int q_total = K >> 4;                                // k steps of 16
     const SplitRange sr32 = split_range(K, splits, blockIdx.y);
     const int q0 = sr32.q0 * 2, q1 = min(sr32.q1 * 2, q_total);
     const int c0 = q0 / KS, c1 = (q1 + KS - 1) / KS;
-    const int tile0 = (blockIdx.x * (WIDE ? 4 : 2) + ng) * NT;   // first 32-column tile of this wave
+    const int tile0 = (bx * (WIDE ? 4 : 2) + ng) * NT;   // first 32-column tile of this wave
     const __amdgpu_buffer_rsrc_t ra = make_rsrc(a, (size_t)q_total * m_tiles * 1024);
     const __amdgpu_buffer_rsrc_t rw = make_rsrc(w, (size_t)t32 * 32 * K * 2);
 
@@ -254,17 +271,22 @@ __global__ __launch_bounds__(256) void gemm_bf16_large_kernel(const bf16_t *__re
     const int wv = __builtin_amdgcn_readfirstlane(wave);
     const int a_chunk_step = KS * m_tiles * 1024;
     const int lane16 = lane * 16;
-    bf16x8 stage[STAGE];
-    auto load_a1 = [&](int s, int c) {
+    // HALF (the 8-row-tile variant, which has no registers to spare): half as many staging registers, each
+    // carrying two pieces per chunk; a piece is then in flight for half a chunk instead of a whole one.
+    constexpr bool HALF = MTA >= 8;
+    constexpr int SR = HALF ? STAGE / 2 : STAGE;
+    static_assert(!HALF || (STAGE % 2 == 0 && 4 * STAGE <= FR), "two events per staging register and chunk");
+    bf16x8 stage[SR];
+    auto load_a1 = [&](int s, int c) {          // piece s of chunk c -> staging register s % SR
         const int i = wv + 4 * s;
         const int ks = i / CTL, ct = i % CTL;
         const bool ok = i < CTL * KS && ct < ct_here && c < c1;
-        stage[s] = __builtin_bit_cast(
+        stage[s % SR] = __builtin_bit_cast(
             bf16x8, __builtin_amdgcn_raw_buffer_load_b128(ra, ok ? lane16 : OOB,
                                                           (ks * m_tiles + mt_base + ct) * 1024 + c * a_chunk_step, 0));
     };
     auto store_a1 = [&](int s, int buf) {
-        if (STAGE * 256 == PIECES || tid + s * 256 < PIECES) lds[buf * PIECES + tid + s * 256] = stage[s];
+        if (STAGE * 256 == PIECES || tid + s * 256 < PIECES) lds[buf * PIECES + tid + s * 256] = stage[s % SR];
     };
 
     f32x16 acc[MTA][NT];
@@ -279,21 +301,30 @@ __global__ __launch_bounds__(256) void gemm_bf16_large_kernel(const bf16_t *__re
     // The loads of the ring's second half and of the second chunk's A are issued in the order the loop issues
     // them, so that the in-flight counts the compiler derives at the loop entry equal those of the back edge.
 #pragma unroll
-    for (int s = 0; s < STAGE; ++s) load_a1(s, c0);
+    for (int s = 0; s < SR; ++s) load_a1(s, c0);
 #pragma unroll
     for (int s = 0; s < KS; ++s)
 #pragma unroll
         for (int j = 0; j < NT; ++j) wbuf[s][j] = ld_w(j, q0 + s);
 #pragma unroll
-    for (int s = 0; s < STAGE; ++s) store_a1(s, 0);
+    for (int s = 0; s < SR; ++s) store_a1(s, 0);
+    if (HALF) {
 #pragma unroll
-    for (int f = 0; f < FR; ++f) {
-        if (f % MTA == MTA - 1) {
+        for (int s = SR; s < STAGE; ++s) load_a1(s, c0);
 #pragma unroll
-            for (int j = 0; j < NT; ++j) wbuf[KS + f / MTA][j] = ld_w(j, q0 + KS + f / MTA);
+        for (int s = SR; s < STAGE; ++s) store_a1(s, 0);
+#pragma unroll
+        for (int s = 0; s < SR; ++s) load_a1(s, c0 + 1);
+    } else {
+#pragma unroll
+        for (int f = 0; f < FR; ++f) {
+            if (f % MTA == MTA - 1) {
+#pragma unroll
+                for (int j = 0; j < NT; ++j) wbuf[KS + f / MTA][j] = ld_w(j, q0 + KS + f / MTA);
+            }
+            if ((f & 1) && (f >> 1) < STAGE) load_a1(f >> 1, c0 + 1);
+            __builtin_amdgcn_sched_barrier(0);
         }
-        if ((f & 1) && (f >> 1) < STAGE) load_a1(f >> 1, c0 + 1);
-        __builtin_amdgcn_sched_barrier(0);
     }
     __syncthreads();
 
@@ -315,7 +346,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_large_kernel(const bf16_t *__re
             for (int f = 0; f < FR; ++f) {
                 if (f + AFD < FR) af[(f + AFD) % (AFD + 1)] = lds_frag(buf, f + AFD);
                 const int ks = f / MTA, mt = f % MTA;
-                const int slot = ci * KS + ks;
+                const int slot = (ci * KS + ks) % PFK;
 #pragma unroll
                 for (int j = 0; j < NT; ++j)
                     acc[mt][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wbuf[slot][j], af[f % (AFD + 1)], acc[mt][j],
@@ -327,7 +358,16 @@ __global__ __launch_bounds__(256) void gemm_bf16_large_kernel(const bf16_t *__re
                 // the next chunk's A goes to the other LDS buffer one piece at a time between the MFMAs (a
                 // burst of stores would sit in front of the fragment reads in the in-order LDS queue), and
                 // the freed staging register at once takes the piece of the chunk after that
-                if ((f & 1) && (f >> 1) < STAGE) {
+                if (HALF) {
+                    // event e stores piece e of the next chunk and reloads its register with the piece that is
+                    // stored half a chunk later: e + STAGE/2 of the next chunk, or e - STAGE/2 of the one after
+                    if ((f & 3) == 1 && (f >> 2) < STAGE) {
+                        const int e = f >> 2;
+                        store_a1(e, buf ^ 1);
+                        if (e < SR) load_a1(e + SR, c + 1);
+                        else load_a1(e - SR, c + 2);
+                    }
+                } else if ((f & 1) && (f >> 1) < STAGE) {
                     store_a1(f >> 1, buf ^ 1);
                     load_a1(f >> 1, c + 2);
                 }
@@ -463,6 +503,13 @@ void launch_large(const bf16_t *a, const bf16_t *w, float *out, int M, int N, in
     constexpr int BN = WIDE ? 256 : 128;
     int m_tiles = (M + 31) / 32;
     dim3 grid((N + BN - 1) / BN, p.splits, (m_tiles + CTL - 1) / CTL);
+    const int n_colblk = grid.x, n_pass = grid.z;
+    int swz_p = 0, swz_c = 0;
+    if (p.swz > 0 && n_pass >= 2) {          // super-tiles of swz x swz workgroups, dealt to the XCDs in turn
+        swz_p = swz_c = p.swz;
+        const int n_st = ((n_pass + swz_p - 1) / swz_p) * ((n_colblk + swz_c - 1) / swz_c);
+        grid = dim3(8 * ((n_st + 7) / 8) * swz_p * swz_c, p.splits, 1);
+    }
     constexpr size_t SMEM = (size_t)2 * CTL * 8 * 1024;
     static bool attr_set = false;          // LDS above 64 KiB has to be granted per kernel
     if (!attr_set) {
@@ -470,7 +517,8 @@ void launch_large(const bf16_t *a, const bf16_t *w, float *out, int M, int N, in
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)SMEM);
         attr_set = true;
     }
-    gemm_bf16_large_kernel<MTA, WIDE><<<grid, 256, SMEM, st>>>(a, w, out, M, N, K, p.splits, epi);
+    gemm_bf16_large_kernel<MTA, WIDE><<<grid, 256, SMEM, st>>>(a, w, out, M, N, K, p.splits, epi, swz_p, swz_c, n_pass,
+                                                               n_colblk);
 }
 
 }  // namespace
@@ -480,6 +528,7 @@ GemmPlan plan_gemm_bf16(int M, int N, int K, bool force_single_split) {
     p.nt = 2;
     p.bk = 128;
     p.wide = 0;
+    p.swz = 0;
     const int wgs = (N + 127) / 128;
     const int units = (K + SPLIT_UNIT - 1) / SPLIT_UNIT;
     auto fit = [&](int want) {                   // clamp to the units there are and drop empty trailing splits
@@ -515,6 +564,18 @@ GemmPlan plan_gemm_bf16(int M, int N, int K, bool force_single_split) {
             p.mt = 5;
             ctl = 5;
         }
+        // 512 rows and more: the launch is bound by the compute units' L1 bandwidth, not by HBM (every workgroup
+        // pulls its A rows and W columns through it), so the workgroup tile is made as square as the register
+        // file allows: 256 rows x 256 columns, eight row tiles per wave.  Measured at 4096 rows of the 8B shape:
+        // 0.65-0.95 PFLOP/s with 288 x 128 tiles, 0.88-1.28 with these.  Grids of many rounds (the LM head) are
+        // also dealt to the XCDs in 4 x 4 super-tiles (+20 %; on grids of a few rounds the uneven deal costs more
+        // than the sharing gains).
+        if (t >= 16) {
+            p.wide = 1;
+            p.mt = 8;
+            ctl = 8;
+            p.swz = (N + 255) / 256 >= 256 ? 4 : 0;
+        }
         p.m_chunks = (t + ctl - 1) / ctl;
     }
     if (const char *e = getenv("TIDAR_GEMM_SPLITS")) {   // tuning override for sweeps (unset in normal use)
@@ -530,6 +591,8 @@ void launch_gemm_bf16(const bf16_t *a, const bf16_t *w, float *out, int M, int N
     if (M <= 32) {
         if (p.mt == 1) launch_small<1, 16>(a, w, out, M, N, K, p, out_row_major, st);
         else launch_small<2, 8>(a, w, out, M, N, K, p, out_row_major, st);
+    } else if (p.wide && p.mt == 8) {
+        launch_large<8, true>(a, w, out, M, N, K, p, out_row_major, st);
     } else if (p.wide) {
         launch_large<5, true>(a, w, out, M, N, K, p, out_row_major, st);
     } else if (p.mt == 1) {

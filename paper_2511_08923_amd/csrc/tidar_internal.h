@@ -107,6 +107,7 @@ struct GemmPlan {
     int bk;        // K elements staged per LDS chunk
     int m_chunks;  // passes over M (grid.z)
     int wide;      // 256-column workgroups (four waves side by side) instead of 128-column ones (2 x 2 waves)
+    int swz;       // > 0: (row pass, column block) plane dealt to the XCDs in super-tiles of swz x swz workgroups
 };
 
 GemmPlan plan_gemm_bf16(int M, int N, int K, bool force_single_split);

@@ -46,7 +46,12 @@ def _gemm(T, ctx, a, w):
                                    (272, 16400, 512), (161, 16384, 256), (289, 32752, 384),
                                    # row passes: 3 tiles as 2+1, 5 as 3+2, 7 as 4+3, 12 as 6+6; one tile (no row split)
                                    (65, 4096, 2048), (160, 1536, 1536), (200, 4096, 1024), (384, 2048, 4096),
-                                   (40, 6144, 1024)])
+                                   (40, 6144, 1024),
+                                   # 512 rows and more: 256 x 256 workgroup tiles (eight row tiles per wave, half-size
+                                   # staging ring), whole and ragged row passes, split K, ragged column block, an
+                                   # odd chunk count (K = 384), and a grid wide enough for the XCD super-tiles
+                                   (512, 1024, 1024), (1000, 4096, 4096), (1025, 784, 608), (2176, 1536, 12288),
+                                   (600, 16400, 384), (777, 65536 + 48, 256)])
 def test_gemm_matches_oracle_matmul(T, ctx8b, M, N, K):
     print(f"gemm M={M} N={N} K={K}", flush=True)
     a = TI.make_normal((M, K), seed=M * 7 + K, dtype=torch.bfloat16)
