@@ -394,10 +394,28 @@ AttnPlan plan_attention(int B, int n_kv, int group, int R, int max_keys) {
     p.n_chunks = (TQ + p.tiles_per_chunk - 1) / p.tiles_per_chunk;
     int base = B * n_kv * p.n_chunks;
     int iters = (max_keys + 31) / 32;
-    int s = 512 / base;                       // two resident workgroups per CU: never more than one round
-    if (s > 64) s = 64;
+    // Two workgroups are resident per CU (512 slots).  A split costs about eight key-pair iterations of prologue
+    // and partial-sum epilogue; a grid of w slot-fulls takes about w + 1/2 workgroup times (the last round is
+    // ragged).  The split count with the least estimated time wins, the smaller one on a near tie (fewer partial
+    // sums for the combine kernel): 7 at batch 1 and 4096 keys (one full round), 5 at batch 4 and 8192 keys
+    // (where one split left 44 % of the slots idle for the whole launch), 1 once the batch alone fills the chip
+    // several times over.
+    // No more than 64 splits (the combine kernel reads one per lane) and, beyond two, no more than four slot-fulls
+    // of workgroups: that bound depends on the row structure alone, and the workspace is sized by it, so the
+    // partial-sum area does not depend on the key bound of a particular call.
+    p.splits_bound = 2048 / base < 2 ? 2 : 2048 / base > 64 ? 64 : 2048 / base;
     int cap = (iters + 3) / 4;                // at least four key pairs per split
-    if (s > cap) s = cap;
+    if (cap > p.splits_bound) cap = p.splits_bound;
+    int s = 1;
+    double best = 0.0;
+    for (int c = 1; c <= cap; ++c) {
+        const double waves = (double)base * c / 512.0;
+        const double cost = (waves <= 1.0 ? 1.0 : waves + 0.5) * ((iters + c - 1) / c + 8);
+        if (c == 1 || cost < 0.97 * best) {
+            best = cost;
+            s = c;
+        }
+    }
     p.splits = s < 1 ? 1 : s;
     if (const char *e = getenv("TIDAR_ATTN_SPLITS")) {     // tuning override for sweeps (unset in normal use)
         int v = atoi(e);

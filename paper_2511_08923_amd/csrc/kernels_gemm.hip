@@ -219,7 +219,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_large_kernel(const bf16_t *__re
                                                               int M, int N, int K, int splits, int epi,
                                                               int swz_p, int swz_c, int n_pass, int n_colblk) {
     constexpr int NT = 2, KS = 8;
-    constexpr int PFK = MTA >= 8 ? KS : 2 * KS;  // weight ring depth in k steps: one chunk or two
+    constexpr bool BIG = WIDE && MTA >= 6;       // the many-row variants: registers go to the accumulators
+    constexpr int PFK = BIG ? KS : 2 * KS;       // weight ring depth in k steps: one chunk or two
     constexpr int CTL = WIDE ? MTA : (MTA == 5) ? 9 : 2 * MTA;
     // Many row passes: the (pass, column block) plane is cut into super-tiles of swz_p x swz_c workgroups, each
     // handed whole to one XCD (workgroup i of a launch runs on XCD i % 8), passes fastest: the workgroups that
@@ -271,9 +272,9 @@ __global__ __launch_bounds__(256) void gemm_bf16_large_kernel(const bf16_t *__re
     const int wv = __builtin_amdgcn_readfirstlane(wave);
     const int a_chunk_step = KS * m_tiles * 1024;
     const int lane16 = lane * 16;
-    // HALF (the 8-row-tile variant, which has no registers to spare): half as many staging registers, each
+    // HALF (the many-row variants, which have no registers to spare): half as many staging registers, each
     // carrying two pieces per chunk; a piece is then in flight for half a chunk instead of a whole one.
-    constexpr bool HALF = MTA >= 8;
+    constexpr bool HALF = BIG;
     constexpr int SR = HALF ? STAGE / 2 : STAGE;
     static_assert(!HALF || (STAGE % 2 == 0 && 4 * STAGE <= FR), "two events per staging register and chunk");
     bf16x8 stage[SR];
@@ -566,14 +567,14 @@ GemmPlan plan_gemm_bf16(int M, int N, int K, bool force_single_split) {
         }
         // 512 rows and more: the launch is bound by the compute units' L1 bandwidth, not by HBM (every workgroup
         // pulls its A rows and W columns through it), so the workgroup tile is made as square as the register
-        // file allows: 256 rows x 256 columns, eight row tiles per wave.  Measured at 4096 rows of the 8B shape:
+        // file allows: up to 256 rows x 256 columns, eight row tiles per wave.  Measured at 4096 rows of the 8B shape:
         // 0.65-0.95 PFLOP/s with 288 x 128 tiles, 0.88-1.28 with these.  Grids of many rounds (the LM head) are
         // also dealt to the XCDs in 4 x 4 super-tiles (+20 %; on grids of a few rounds the uneven deal costs more
         // than the sharing gains).
         if (t >= 16) {
             p.wide = 1;
-            p.mt = 8;
-            ctl = 8;
+            const int passes = (t + 7) / 8;
+            p.mt = ctl = (t + passes - 1) / passes;      // 6, 7 or 8 row tiles per pass: the passes come out even
             p.swz = (N + 255) / 256 >= 256 ? 4 : 0;
         }
         p.m_chunks = (t + ctl - 1) / ctl;
@@ -593,6 +594,10 @@ void launch_gemm_bf16(const bf16_t *a, const bf16_t *w, float *out, int M, int N
         else launch_small<2, 8>(a, w, out, M, N, K, p, out_row_major, st);
     } else if (p.wide && p.mt == 8) {
         launch_large<8, true>(a, w, out, M, N, K, p, out_row_major, st);
+    } else if (p.wide && p.mt == 7) {
+        launch_large<7, true>(a, w, out, M, N, K, p, out_row_major, st);
+    } else if (p.wide && p.mt == 6) {
+        launch_large<6, true>(a, w, out, M, N, K, p, out_row_major, st);
     } else if (p.wide) {
         launch_large<5, true>(a, w, out, M, N, K, p, out_row_major, st);
     } else if (p.mt == 1) {

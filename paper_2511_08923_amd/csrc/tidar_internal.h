@@ -151,6 +151,7 @@ void launch_place_kv(int dtype, const void *k_new, const void *v_new, const int3
 
 struct AttnPlan {
     int splits;
+    int splits_bound;    // the most splits any key bound can give this row structure (sizes the workspace)
     int n_chunks;        // q-tile chunks per kv head
     int tiles_per_chunk;
     int per;             // key-pair iterations per split, from the caller's bound on the key count (not from the

@@ -116,7 +116,7 @@ Layout make_layout(const tidar_config &c, int B, int R, int n_mask, int Mh, int 
     if (c.dtype == TIDAR_BF16) {
         AttnPlan ap = plan_attention(B, c.n_kv_heads, c.n_q_heads / c.n_kv_heads, R, max_keys);
         l.attn_splits = ap.splits;
-        pf = attn_partial_floats(B, c.n_kv_heads, c.n_q_heads / c.n_kv_heads, R, c.head_dim, ap.splits);
+        pf = attn_partial_floats(B, c.n_kv_heads, c.n_q_heads / c.n_kv_heads, R, c.head_dim, ap.splits_bound);
     }
     l.attn_part = take(pf * 4);
     l.o = take(af_elems(M, q_dim) * es);
@@ -669,7 +669,8 @@ tidar_status tidar_hybrid_attention(tidar_ctx *ctx, const tidar_kv_cache *kv, in
     int max_keys = max_prefix_len_hint + d.R;
     AttnPlan ap = plan_attention(batch, c.n_kv_heads, c.n_q_heads / c.n_kv_heads, d.R, max_keys);
     size_t pf = c.dtype == TIDAR_BF16
-                    ? attn_partial_floats(batch, c.n_kv_heads, c.n_q_heads / c.n_kv_heads, d.R, c.head_dim, ap.splits)
+                    ? attn_partial_floats(batch, c.n_kv_heads, c.n_q_heads / c.n_kv_heads, d.R, c.head_dim,
+                                          ap.splits_bound)
                     : 0;
     if (2 * scr + align_up(pf * 4) > ws_bytes) return TIDAR_ENOMEM;
     char *wsb = (char *)ws;

@@ -51,7 +51,9 @@ def _gemm(T, ctx, a, w):
                                    # staging ring), whole and ragged row passes, split K, ragged column block, an
                                    # odd chunk count (K = 384), and a grid wide enough for the XCD super-tiles
                                    (512, 1024, 1024), (1000, 4096, 4096), (1025, 784, 608), (2176, 1536, 12288),
-                                   (600, 16400, 384), (777, 65536 + 48, 256)])
+                                   (600, 16400, 384), (777, 65536 + 48, 256),
+                                   # six row tiles per pass (17 tiles as 6+6+5, 18 as 6+6+6)
+                                   (544, 2048, 1024), (576, 6144, 512)])
 def test_gemm_matches_oracle_matmul(T, ctx8b, M, N, K):
     print(f"gemm M={M} N={N} K={K}", flush=True)
     a = TI.make_normal((M, K), seed=M * 7 + K, dtype=torch.bfloat16)
