@@ -47,10 +47,12 @@ struct AttnArgs {
     RowDesc d;
     int n_q, group;
     int n_chunks, tiles_per_chunk, splits, per;
-    int inv_bl;                // ceil(65536 / bl)
     int n_pages;               // physical pages per layer (bounds of the page buffers)
     float scale_log2e;
     float *opart, *mpart, *lpart;
+    bf16_t *out;               // single split only: [rows][n_q][HD], or the A-fragment layout (out_af)
+    int out_af;
+    ActLayout lay;
 };
 
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
@@ -293,6 +295,35 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
         __syncthreads();
     }
 
+    // ---- a single split is the whole answer: normalise in registers and store it (a lane holds, for its query
+    // row, 16 runs of four consecutive head-dim values), no partial results and no combine launch
+    if (a.splits == 1) {
+#pragma unroll
+        for (int i = 0; i < QT; ++i) {
+            const int tile = t0 + wave + 4 * i;
+            if (tile >= t1) continue;
+            float l = l_run[i];
+            l += __shfl_xor(l, 32);
+            const int f = tile * 32 + lq;
+            if (f >= F) continue;
+            const float inv = 1.f / l;
+            const int hq = f / d.R, r = f - hq * d.R;
+            const int row = b * d.R + r, col0 = (g * a.group + hq) * HD + 4 * lh;
+            typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    const bf16x4 o = {(bf16_t)(acc[i][dt][4 * r4] * inv), (bf16_t)(acc[i][dt][4 * r4 + 1] * inv),
+                                      (bf16_t)(acc[i][dt][4 * r4 + 2] * inv), (bf16_t)(acc[i][dt][4 * r4 + 3] * inv)};
+                    const int col = col0 + 32 * dt + 8 * r4;
+                    const size_t idx = a.out_af ? af_index(row, col, a.lay) : (size_t)row * a.n_q * HD + col;
+                    *(bf16x4 *)(a.out + idx) = o;
+                }
+        }
+        return;
+    }
+
     // ---- write this split's partial (unnormalised O, reference in log2 units, denominator)
     const size_t pbase = (((size_t)b * a.kv.n_kv + g) * a.splits + split) * F;
 #pragma unroll
@@ -431,8 +462,11 @@ size_t attn_partial_floats(int B, int n_kv, int group, int R, int hd, int splits
 
 void launch_attention_bf16(const bf16_t *q, KvView kv, int n_pages, const bf16_t *k_scr, const bf16_t *v_scr,
                            const int32_t *prefix_len, RowDesc d, int B, int n_q, const AttnPlan &p, float *part,
-                           hipStream_t st) {
+                           bf16_t *out, int out_af, hipStream_t st) {
     AttnArgs a;
+    a.out = out;
+    a.out_af = out_af;
+    a.lay = act_layout(B * d.R);
     a.q = q;
     a.kv = kv;
     a.k_scr = k_scr;
@@ -445,7 +479,6 @@ void launch_attention_bf16(const bf16_t *q, KvView kv, int n_pages, const bf16_t
     a.tiles_per_chunk = p.tiles_per_chunk;
     a.splits = p.splits;
     a.per = p.per;
-    a.inv_bl = d.bl > 0 ? (65536 + d.bl - 1) / d.bl : 0;
     a.n_pages = n_pages;
     a.scale_log2e = 1.4426950408889634f / sqrtf((float)kv.hd);
     size_t F = (size_t)a.group * d.R;
@@ -459,6 +492,7 @@ void launch_attention_bf16(const bf16_t *q, KvView kv, int n_pages, const bf16_t
 
 void launch_attention_combine(const float *part, int B, int R, int n_q, int n_kv, int hd, int splits, bf16_t *out,
                               int out_af, hipStream_t st) {
+    if (splits == 1) return;                  // the attention kernel has written the result itself
     size_t F = (size_t)(n_q / n_kv) * R;
     size_t rows = (size_t)B * n_kv * splits * F;
     attn_combine_kernel<<<dim3(B * R, n_q), 64, 0, st>>>(part, part + rows * hd, part + rows * hd + rows, R, n_q, n_kv,

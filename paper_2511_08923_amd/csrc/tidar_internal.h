@@ -160,9 +160,12 @@ struct AttnPlan {
 AttnPlan plan_attention(int B, int n_kv, int group, int R, int max_keys);
 size_t attn_partial_floats(int B, int n_kv, int group, int R, int hd, int splits);
 
+// With one split the kernel writes the result to out (row-major [rows][n_q][hd], or, out_af != 0, the A-fragment
+// layout over B * R rows) and launch_attention_combine does nothing; with more it writes per-split partial
+// results to part, which launch_attention_combine folds into out.
 void launch_attention_bf16(const bf16_t *q, KvView kv, int n_pages, const bf16_t *k_scr, const bf16_t *v_scr,
                            const int32_t *prefix_len, RowDesc d, int B, int n_q, const AttnPlan &p, float *part,
-                           hipStream_t st);
+                           bf16_t *out, int out_af, hipStream_t st);
 void launch_attention_combine(const float *part, int B, int R, int n_q, int n_kv, int hd, int splits, bf16_t *out,
                               int out_af, hipStream_t st);
 void launch_attention_f32(const float *q, KvView kv, const float *k_scr, const float *v_scr,

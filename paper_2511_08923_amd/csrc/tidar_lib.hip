@@ -205,9 +205,9 @@ void attention(tidar_ctx *ctx, const Layout &l, char *ws, KvView kvv, int n_page
             Prof p(ctx, KC_ATTN, st);
             launch_attention_bf16((const bf16_t *)(ws + l.q), kvv, n_pages, (const bf16_t *)(ws + l.k_scr),
                                   (const bf16_t *)(ws + l.v_scr), prefix_len, d, B, c.n_q_heads, ap,
-                                  (float *)(ws + l.attn_part), st);
+                                  (float *)(ws + l.attn_part), (bf16_t *)o_out, 1, st);
         }
-        {
+        if (ap.splits > 1) {
             Prof p(ctx, KC_ATTN_COMBINE, st);
             launch_attention_combine((const float *)(ws + l.attn_part), B, d.R, c.n_q_heads, c.n_kv_heads, c.head_dim,
                                      ap.splits, (bf16_t *)o_out, 1, st);
@@ -685,8 +685,9 @@ tidar_status tidar_hybrid_attention(tidar_ctx *ctx, const tidar_kv_cache *kv, in
             Prof p(ctx, KC_ATTN, st);
             launch_attention_bf16((const bf16_t *)q, kvv, kv->n_pages, (const bf16_t *)wsb,
                                   (const bf16_t *)(wsb + scr), prefix_len, d, batch, c.n_q_heads, ap,
-                                  (float *)(wsb + 2 * scr), st);
+                                  (float *)(wsb + 2 * scr), (bf16_t *)out, 0, st);
         }
+        if (ap.splits == 1) return TIDAR_OK;
         Prof p(ctx, KC_ATTN_COMBINE, st);
         launch_attention_combine((const float *)(wsb + 2 * scr), batch, d.R, c.n_q_heads, c.n_kv_heads, c.head_dim,
                                  ap.splits, (bf16_t *)out, 0, st);
