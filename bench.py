@@ -51,6 +51,10 @@ def parse():
                          "(one JSON line per point on stdout)")
     ap.add_argument("--sweep-batches", type=str, default="1,4,8,16,32")
     ap.add_argument("--sweep-ks", type=str, default="4,8,16")
+    ap.add_argument("--score-bench", action="store_true",
+                    help="time the many-row entry points on a --prefix-token text: tidar_prefill, tidar_score with the "
+                         "causal section only (AR-mode likelihood) and with the mask section (training layout, block "
+                         "length --k), with the per-kernel-class split of each")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain device copy of 1 GiB ten times (known traffic: 1 GiB read + 1 GiB written "
                          "per launch) so that rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings can be scaled")
@@ -164,6 +168,40 @@ def attention_microbench(args, torch, T, TI, dev):
                       "data": "synthetic N(0,1) Q/K/V, 16 rotating caches, shuffled page table"}))
 
 
+def score_bench(args, shape, torch, T, TI, dev):
+    """Prefill, AR-mode scoring and the training-layout forward over one synthetic text of --prefix tokens: whole-call
+    wall time between two synchronisations (second of two calls) and the HIP-event time per kernel class."""
+    S, k = args.prefix, args.k
+    w = TI.make_weights(shape, seed=4, dtype=torch.bfloat16, device=dev)
+    eng = T.Engine(shape, w, dtype=T.TIDAR_BF16, max_k=k, max_batch=1, max_seq_len=S + 4 * k, device=dev,
+                   free_source=True)
+    del w
+    text = TI.make_prompt(shape, S, seed=5).to(dev)
+    out = {}
+    calls = (("prefill", lambda: eng.prefill(text, k)),
+             ("score_causal", lambda: eng.score(text, block_len=0)),
+             ("score_training_layout", lambda: eng.score(text, block_len=k)))
+    for name, call in calls:
+        for _ in range(2):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            res = call()
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t0
+        T.tidar_profile_reset(eng.ctx)
+        T.tidar_profile_enable(eng.ctx, True)
+        call()
+        torch.cuda.synchronize()
+        pr = T.tidar_profile_read(eng.ctx)
+        T.tidar_profile_enable(eng.ctx, False)
+        out[name] = {"ms": dt * 1e3, "tokens_per_s": S / dt,
+                     "kernel_class_ms": {n: round(v["ms"], 2) for n, v in sorted(pr.items(), key=lambda kv: -kv[1]["ms"])}}
+        if name != "prefill":
+            out[name]["loss"] = float(res[2][0])
+    print(json.dumps({"score_bench": out, "tokens": S, "block_len": k, "shape": shape.name, "layers": shape.n_layers,
+                      "dtype": "bf16", "data": "synthetic uniform token ids, random-init weights"}))
+
+
 def sweep(args, shape, torch, T, TI, dev):
     """TiDAR-step vs AR-step latency over batch and block length (the free-slot regime and its crossover).
     The cache is filled synthetically (N(0,1) K/V, as in the attention micro-benchmark): step latency does not
@@ -270,6 +308,8 @@ def main():
         return attention_microbench(args, torch, T, TI, dev)
     if args.sweep:
         return sweep(args, shape, torch, T, TI, dev)
+    if args.score_bench:
+        return score_bench(args, shape, torch, T, TI, dev)
     k, P, V = args.k, args.prefix, shape.vocab
     R = k * (k + 1)
     n_timed = args.steps + args.warmup

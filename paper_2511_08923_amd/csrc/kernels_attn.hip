@@ -162,6 +162,39 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
     const int TQ = (F + 31) >> 5;
     const int t0 = chunk * a.tiles_per_chunk;
     const int t1 = min(TQ, t0 + a.tiles_per_chunk);
+    // Key-pair iterations this workgroup can need at all: cache units up to the furthest key any of its rows
+    // sees, then the mask units of its rows' own blocks.  (Rows of one query head only; a workgroup that straddles
+    // two heads keeps the whole range.)  Inside a prefill or scoring pass most of the range falls away: causal
+    // rows see neither the later rows of the pass nor any mask row, a mask block only the text before it and
+    // itself.  Iterations are dropped whole, so the pairing of keys into iterations and splits is untouched.
+    int itA1 = n_it, itB0 = n_it, itB1 = n_it;       // [it0, itA1) and [itB0, itB1), itA1 <= itB0
+    {
+        const int f_lo = t0 * 32, f_hi = min(F, t1 * 32) - 1;
+        const int h_lo = f_lo / d.R, h_hi = f_hi / d.R;
+        if (h_lo == h_hi) {
+            const int r_lo = f_lo - h_lo * d.R, r_hi = f_hi - h_lo * d.R;
+            int vis_max = min(r_hi, d.nc - 1) + 1;                       // the causal rows among them
+            int um0 = 0, um1 = 0;                                        // mask units [um0, um1)
+            if (r_hi >= d.nc) {
+                const int j_lo = (max(r_lo, d.nc) - d.nc) / d.bl, j_hi = (r_hi - d.nc) / d.bl;
+                if (r_lo >= d.nc) vis_max = 0;
+                vis_max = max(vis_max, d.cond0 + j_hi * d.cstride);
+                um0 = (j_lo * d.bl) >> 4;
+                um1 = (min((j_hi + 1) * d.bl, n_mask) + 15) >> 4;
+            }
+            const int uc1 = min(n_cache_units, (L + min(vis_max, d.nc) + 15) >> 4);
+            itA1 = (uc1 + 1) >> 1;
+            itB0 = max(itA1, (n_cache_units + um0) >> 1);
+            itB1 = um1 > um0 ? max(itB0, (n_cache_units + um1 + 1) >> 1) : itB0;
+        } else {
+            itB0 = itB1 = n_it;
+        }
+    }
+    // this split's share of the two ranges, walked as one sequence of nA + nB iterations
+    const int a0 = it0, a1 = max(a0, min(it1, itA1));
+    const int b0 = max(it0, itB0), b1 = max(b0, min(it1, itB1));
+    const int nA = a1 - a0, n_seq = nA + (b1 - b0);
+    auto seq_it = [&](int n) { return n < nA ? a0 + n : b0 + (n - nA); };
 
     // ---- this wave's query tiles: Q fragments (B operand: lane = (q row, hd half of the k step)), row info
     bf16x8 qf[QT][8];
@@ -206,13 +239,15 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
     const int v_d = tid >> 1, v_half = tid & 1;
     const int k_in = (k_key * HD + k_piece * 8) * 2, v_in = (v_d * 16 + v_half * 8) * 2;   // byte offsets in a unit
     const int32_t *pt = a.kv.page_table + (size_t)(d.seq_base + b) * a.kv.pages_per_seq;
-    auto load_kv = [&](int it) {
+    auto load_kv = [&](int n) {                         // n: position in this workgroup's iteration sequence
+        const int it = seq_it(n);
+        const bool live = n < n_seq;
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
             const int uu = 2 * it + u;
-            const bool in_cache = uu < n_cache_units, in_mask = !in_cache && uu < U && it < it1;
+            const bool in_cache = uu < n_cache_units, in_mask = !in_cache && uu < U && live;
             int base = OOB, valid = 0;
-            if (in_cache && it < it1) {                 // scalar (uniform) selects, no vector branch
+            if (in_cache && live) {                     // scalar (uniform) selects, no vector branch
                 const int page = pt[uu];
                 base = (int)((((size_t)page * a.kv.n_kv + g) * 16 * HD) * 2);
                 valid = min(16, L + d.nc - 16 * uu);
@@ -248,13 +283,14 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
         }
     };
 
-    load_kv(it0);
+    load_kv(0);
     store_kv(0);
     __syncthreads();
 
-    for (int it = it0; it < it1; ++it) {
-        const int buf = (it - it0) & 1;
-        load_kv(it + 1);
+    for (int n = 0; n < n_seq; ++n) {
+        const int it = seq_it(n);
+        const int buf = n & 1;
+        load_kv(n + 1);
 
         const bool pure = (2 * it + 1) < n_pure;
 #pragma unroll
