@@ -555,3 +555,69 @@ def test_sampling_bf16_seeded_step_matches_oracle(T, small):
         assert float(pert.max() - pert[int(nxt[0, 0])]) < 2 * err + 1e-5
     else:
         assert int(a[0]) == a_o
+
+
+def test_tiny_fp32_continuous_batching_with_per_sequence_block_length(T):
+    """Sequences that join late and decode with different block lengths: a call covers a run of sequences that share
+    k, selected by offsetting the per-sequence arrays and the page-table pointer (the library keeps no per-sequence
+    state).  Sequences 0 and 1 start together with k = 4; sequence 2 joins after their first step and decodes with
+    k = 8; later sequence 1 moves to the k = 8 group (its four drafts padded with arbitrary tokens, which are
+    rejected).  Every stream must equal the oracle's plain AR decode."""
+    sh = TI.TINY
+    w = TI.make_weights(sh, seed=1)
+    eng = T.Engine(sh, w, dtype=T.TIDAR_F32, max_k=8, max_batch=3, max_seq_len=256)
+    model = O.OracleModel(sh, w)
+    n = 30
+    lens = [33, 20, 47]
+    prompts = torch.zeros(3, 47, dtype=torch.int32)
+    for b, P in enumerate(lens):
+        prompts[b, :P] = TI.make_prompt(sh, P, seed=90 + b)[0]
+    want = [model.ar_decode([int(t) for t in prompts[b, :lens[b]]], n + 16) for b in range(3)]
+    prompts_d = prompts.cuda()
+    mode = T.make_mode()
+    i32 = dict(dtype=torch.int32, device="cuda")
+
+    def kv_from(b0):
+        return T.tidar_kv_cache(eng.k_pages.data_ptr(), eng.v_pages.data_ptr(),
+                                eng.page_table.data_ptr() + b0 * eng.pages_per_seq * 4, eng.pages_per_seq, eng.n_pages)
+
+    got = [[], [], []]
+    drafts = [None, None, None]
+
+    def prefill(b0, nb, k):
+        first = torch.empty(nb, k, **i32)
+        T.tidar_prefill(eng.ctx, eng.w, kv_from(b0), nb, prompts_d[b0:b0 + nb], lens[b0:b0 + nb], k, mode,
+                        eng.prefix_len[b0:b0 + nb], first, None, eng.ws)
+        torch.cuda.synchronize()
+        for i in range(nb):
+            drafts[b0 + i] = first[i].tolist()
+
+    def step(b0, nb, k):
+        d = torch.zeros(nb, k, **i32)
+        for i in range(nb):
+            cur = drafts[b0 + i][:k]
+            d[i] = torch.tensor(cur + [7] * (k - len(cur)), **i32)      # pad: slot 0 is what counts
+        a = torch.empty(nb, **i32)
+        acc = torch.empty(nb, k, **i32)
+        nxt = torch.empty(nb, k, **i32)
+        hint = int(eng.prefix_len[b0:b0 + nb].max())
+        T.tidar_step(eng.ctx, eng.w, kv_from(b0), nb, eng.prefix_len[b0:b0 + nb], d, k, mode, a, acc, nxt, None, hint,
+                     eng.ws)
+        torch.cuda.synchronize()
+        for i in range(nb):
+            got[b0 + i] += acc[i, :int(a[i])].tolist()
+            drafts[b0 + i] = nxt[i].tolist()
+
+    prefill(0, 2, 4)
+    step(0, 2, 4)
+    prefill(2, 1, 8)                       # sequence 2 joins
+    for _ in range(3):
+        step(0, 2, 4)
+        step(2, 1, 8)
+    while min(len(g) for g in got) < n:    # sequence 1 now decodes with the longer block
+        step(0, 1, 4)
+        step(1, 2, 8)
+    for b in range(3):
+        assert got[b] == want[b][:len(got[b])], b
+        assert int(eng.prefix_len[b]) == lens[b] + len(got[b])
+    eng.close()
