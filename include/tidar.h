@@ -178,7 +178,8 @@ tidar_status tidar_prefill(tidar_ctx *ctx, const tidar_weights *w, const tidar_k
  * The library keeps no per-sequence state: a call covers sequences 0..batch-1 of the arrays it is given, so a
  * run of sequences inside a larger batch is addressed by offsetting prefix_len, drafts, the outputs and
  * kv->page_table (by pages_per_seq entries per sequence).  That is how sequences with different k are stepped
- * (one call per run of equal k), join (tidar_prefill on their own slots) and leave.
+ * (one call per run of equal k), join (tidar_prefill on their own slots) and leave.  (Sampling noise is keyed by
+ * the sequence's index within the call: a sampled stream is reproducible only while that index stays the same.)
  */
 tidar_status tidar_step(tidar_ctx *ctx, const tidar_weights *w, const tidar_kv_cache *kv, int32_t batch,
                         int32_t *prefix_len, const int32_t *drafts, int32_t k, const tidar_mode *mode,
