@@ -2,41 +2,65 @@
 //
 // Work item = (sequence, kv head, chunk of 32-row query tiles, split of the key range).  The query rows of a
 // kv head are the rows of all query heads in its group, flattened (head-in-group major), so a K/V tile that
-// is staged once in LDS serves every query head that shares it.  Four waves split the query tiles; each wave
+// is brought into LDS once serves every query head that shares it.  Four waves split the query tiles; each wave
 // keeps its Q fragments, its O^T accumulators and its softmax state in registers for the whole key range.
 //
 // MFMA: v_mfma_f32_32x32x16_bf16 (on gfx950 twice the rate of the 16x16x32 form).  Scores are formed
 // transposed, S^T[key][q] = K . Q^T, so that in the result layout a lane holds one query column and 16 of the
-// 32 keys of a block: register i <-> key 8*(i/4) + 4*(lane/32) + i%4.  Registers 0-7 (keys of the first page of
-// the pair) and 8-15 (second page) are, after exponentiation and without any data movement, the B operands
-// (P^T) of two MFMAs O^T[d][q] += V^T[d][key] . P^T[key][q]; V is kept transposed in HBM ([head_dim][16
-// tokens] per page) and its LDS rows are written with the four-key groups permuted so that the matching A
-// operand is one 16-byte read.
+// 32 keys of a block.  After exponentiation and without any data movement a lane's registers 0-7 (first page of
+// the pair) and 8-15 (second page) are the B operands (P^T) of two MFMAs O^T[d][q] += V^T[d][key] . P^T[key][q];
+// V is kept transposed in HBM ([head_dim][16 tokens] per page).
+//
+// K/V tiles go from HBM straight into LDS (buffer_load ... lds, 16 bytes per lane), three buffers deep, two
+// key-pair iterations ahead of their use: no staging registers, no LDS stores, and the loads of a tile have two
+// iterations to arrive.  A wave's lanes choose *which* 16 bytes they fetch, which is where the LDS layout comes
+// from: K rows of 256 bytes whose 16-byte pieces are XOR-swizzled by the row (conflict-free fragment reads without
+// padding), rows 4-7 and 8-11 of a unit exchanged so that a lane's score registers of a unit are eight consecutive
+// keys, the same eight that one 16-byte piece of V^T holds.
 //
 // Softmax numerators are taken against an integral power-of-two reference (ceil of the running maximum in
-// log2 units): their bf16 rounding is then independent of the reference in force, i.e. of tiling and splits,
-// every rescale is exact, and the reference moves so rarely that the rescale of O^T is skipped almost always.
+// log2 units): their bf16 rounding is then independent of the reference in force, i.e. of tiling and splits, and
+// every rescale is exact.  While the keys are plain prefix keys the reference is not even moved (see
+// attn_block_fixed_ref): the loop then has no rescale arm at all.
 //
 // Keys come in units of 16: cache pages 0 .. ceil((L+nc)/16)-1, then the mask rows' scratch tiles.  Pages that
 // lie wholly below L need no mask at all (every row sees the whole prefix); everything else goes through the
 // (row, key) predicate and a per-(query tile, key pair) skip when nothing is visible.
 #include <stdlib.h>
 
+#include <type_traits>
+
 #include "tidar_internal.h"
 
 namespace {
 
 constexpr int HD = 128;
-constexpr int K_STRIDE = HD + 8;        // bf16 per key row in LDS (+16 B: conflict-free 16-byte reads)
-constexpr int V_STRIDE = 32 + 8;        // bf16 per head-dim row in LDS: 32 keys + pad
-constexpr int OOB = 0x7ffffff0;
+constexpr int TILE = 32 * HD;           // bf16 elements of one K tile (32 keys) and of one V^T tile
 
-__device__ inline __amdgpu_buffer_rsrc_t attn_rsrc(const void *base, size_t bytes) {
-    return __builtin_amdgcn_make_buffer_rsrc((void *)base, 0, (int)(bytes > 0x7fffffe0ull ? 0x7fffffe0ull : bytes),
-                                             0x00020000);
+// 16 bytes per lane straight from a raw buffer into LDS at lds_addr + 16 * lane (the tile's wave-uniform base goes
+// through M0).  Written as inline assembly so that only the explicit vmcnt waits of the kernel order these loads
+// against the LDS reads: issued through the compiler's builtin, every LDS read waits for *all* loads in flight,
+// which is exactly the prefetch this is meant to keep running.
+typedef int int4v __attribute__((ext_vector_type(4)));
+__device__ inline int4v raw_desc(const void *base, size_t bytes) {
+    const unsigned long long p = (unsigned long long)base;
+    return (int4v){(int)(p & 0xffffffffull), (int)((p >> 32) & 0xffffull),
+                   (int)(bytes > 0x7fffffe0ull ? 0x7fffffe0ull : bytes), 0x00020000};
 }
-__device__ inline bf16x8 attn_buf_load(__amdgpu_buffer_rsrc_t r, int byte_off) {
-    return __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, 0));
+// (M0 is a reserved register that the compiler sets itself right before each of its own uses; this kernel has none.)
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+__device__ inline void dma16(unsigned lds_addr, int voff, int4v desc, int soff) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(desc), "s"(soff)
+                 : "memory", "m0");
+}
+#pragma clang diagnostic pop
+__device__ inline void lds_barrier() {       // workgroup barrier for LDS traffic only: global loads stay in flight
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
 }
 
 struct AttnArgs {
@@ -60,9 +84,17 @@ typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 // One 32-query x 32-key block: S^T = K.Q^T, online softmax against the integral reference, O^T += V^T.P^T.
 // c = softmax scale * log2(e).  VIS: bit e set = register e's key is visible to this lane's query row (only read
 // when MASKED).  Kept lean: per score one max, one fma, one v_exp_f32, half a pack and half a dot2.
+// Tile layout in LDS (see the kernel): K rows of 256 bytes with the 16-byte pieces XOR-swizzled by the row, rows
+// 4-7 and 8-11 of a unit exchanged so that score register e of unit u is key 8*(lane/32) + e%8; V^T as
+// [unit][key half][d] 16-byte pieces in natural key order.
 template <bool MASKED>
 __device__ inline void attn_block(const bf16_t *k_lds, const bf16_t *v_lds, int lq, int lh, const bf16x8 (&qf)[8],
                                   f32x16 (&acc)[4], float &m_run, float &l_run, float c, unsigned vis) {
+    const unsigned char *kb = reinterpret_cast<const unsigned char *>(k_lds);
+    const unsigned char *vb = reinterpret_cast<const unsigned char *>(v_lds);
+    // K as A operand: lane = (tile row, hd half of the k step); V^T as A operand: lane = (d, key half of the unit)
+    auto k_frag = [&](int ks) { return *(const bf16x8 *)(kb + lq * 256 + (((2 * ks + lh) ^ (lq & 15)) << 4)); };
+    auto v_frag = [&](int dt, int u) { return *(const bf16x8 *)(vb + (((u * 2 + lh) * 128 + 32 * dt + lq) << 4)); };
     // K as A operand (lane = key, hd half of the k step); fragments are consumed as they arrive.  One
     // accumulation chain: a second one costs 16 registers, and the other resident wave covers the dependency
     f32x16 s;
@@ -70,7 +102,7 @@ __device__ inline void attn_block(const bf16_t *k_lds, const bf16_t *v_lds, int 
     for (int e = 0; e < 16; ++e) s[e] = 0.f;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
-        const bf16x8 kf0 = *(const bf16x8 *)(k_lds + lq * K_STRIDE + 16 * ks + 8 * lh);
+        const bf16x8 kf0 = k_frag(ks);
         s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf0, qf[ks], s, 0, 0, 0);
     }
     // V^T as A operand (lane = d, key chunk): the first half is issued now and is needed after the softmax
@@ -80,7 +112,7 @@ __device__ inline void attn_block(const bf16_t *k_lds, const bf16_t *v_lds, int 
     for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
         for (int u = 0; u < 2; ++u)
-            vf[dt][u] = *(const bf16x8 *)(v_lds + (32 * dt + lq) * V_STRIDE + 16 * u + 8 * lh);
+            vf[dt][u] = v_frag(dt, u);
     float mx = -INFINITY;
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
@@ -90,15 +122,6 @@ __device__ inline void attn_block(const bf16_t *k_lds, const bf16_t *v_lds, int 
     mx = fmaxf(mx, __shfl_xor(mx, 32));
     const float m_new = fmaxf(m_run, ceilf(mx * c));
     const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-    if (__any(m_new != m_run)) {                    // rare after the first blocks: rescale by the exact 2^(old-new)
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
-        l_run *= alpha;
-#pragma unroll
-        for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[dt][e] *= alpha;
-        m_run = m_new;
-    }
     const bf16x2 ones = {(bf16_t)1.0f, (bf16_t)1.0f};
     float psum = 0.f;
     bf16x8 pf[2];
@@ -110,13 +133,89 @@ __device__ inline void attn_block(const bf16_t *k_lds, const bf16_t *v_lds, int 
         pf[e >> 3][e & 7] = pk[0];
         pf[e >> 3][(e & 7) + 1] = pk[1];
     }
+    // O^T += V^T.P^T.  The rescale by the exact 2^(old - new) is rare after the first blocks; it shares its arm of
+    // the branch with a copy of the accumulation so that the common arm updates the accumulators in place (a
+    // rescale arm that rejoined before the MFMAs made the compiler copy all 64 accumulator registers per block)
+    auto accumulate = [&]() __attribute__((always_inline)) {
+        bf16x8 vg[2][2];
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+            for (int u = 0; u < 2; ++u) vg[dt][u] = v_frag(dt + 2, u);
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+                acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt][u], pf[u], acc[dt], 0, 0, 0);
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+                acc[dt + 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vg[dt][u], pf[u], acc[dt + 2], 0, 0, 0);
+    };
+    if (__builtin_expect(__any(m_new != m_run), 0)) {
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
+        l_run = l_run * alpha + psum;
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[dt][e] *= alpha;
+        m_run = m_new;
+        accumulate();
+    } else {
+        l_run += psum;
+        accumulate();
+    }
+}
+
+// The same block for keys that are all visible, against a reference that is *not* moved: the numerators are
+// 2^(s.c - m_run) with the reference of an earlier block, so they may exceed 1 (by less than 2^60, or the block
+// is refused: the caller then runs attn_block, which moves the reference).  bf16 rounding is a matter of the
+// mantissa alone, and every quantity (numerators, denominator, O^T) carries the same power of two, so the
+// normalised result is bit for bit that of the moving reference.  No rescale arm means no branch that rejoins
+// around the accumulators: with one, the compiler copied all 64 accumulator registers twice per block.
+__device__ inline bool attn_block_fixed_ref(const bf16_t *k_lds, const bf16_t *v_lds, int lq, int lh,
+                                            const bf16x8 (&qf)[8], f32x16 (&acc)[4], float m_run, float &l_run,
+                                            float c) {
+    const unsigned char *kb = reinterpret_cast<const unsigned char *>(k_lds);
+    const unsigned char *vb = reinterpret_cast<const unsigned char *>(v_lds);
+    // K as A operand: lane = (tile row, hd half of the k step); V^T as A operand: lane = (d, key half of the unit)
+    auto k_frag = [&](int ks) { return *(const bf16x8 *)(kb + lq * 256 + (((2 * ks + lh) ^ (lq & 15)) << 4)); };
+    auto v_frag = [&](int dt, int u) { return *(const bf16x8 *)(vb + (((u * 2 + lh) * 128 + 32 * dt + lq) << 4)); };
+    f32x16 s;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) s[e] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+        const bf16x8 kf0 = k_frag(ks);
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf0, qf[ks], s, 0, 0, 0);
+    }
+    bf16x8 vf[2][2];
+#pragma unroll
+    for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+        for (int u = 0; u < 2; ++u) vf[dt][u] = v_frag(dt, u);
+    float mx = -INFINITY;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[e]);
+    if (__any(!(mx * c <= m_run + 60.f))) return false;          // also refuses a reference that is still -inf
+    const bf16x2 ones = {(bf16_t)1.0f, (bf16_t)1.0f};
+    float psum = 0.f;
+    bf16x8 pf[2];
+#pragma unroll
+    for (int e = 0; e < 16; e += 2) {
+        bf16x2 pk = {(bf16_t)__builtin_amdgcn_exp2f(fmaf(s[e], c, -m_run)),
+                     (bf16_t)__builtin_amdgcn_exp2f(fmaf(s[e + 1], c, -m_run))};
+        psum = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, psum, false);
+        pf[e >> 3][e & 7] = pk[0];
+        pf[e >> 3][(e & 7) + 1] = pk[1];
+    }
     l_run += psum;
     bf16x8 vg[2][2];
 #pragma unroll
     for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
-        for (int u = 0; u < 2; ++u)
-            vg[dt][u] = *(const bf16x8 *)(v_lds + (32 * (dt + 2) + lq) * V_STRIDE + 16 * u + 8 * lh);
+        for (int u = 0; u < 2; ++u) vg[dt][u] = v_frag(dt + 2, u);
 #pragma unroll
     for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
@@ -127,15 +226,18 @@ __device__ inline void attn_block(const bf16_t *k_lds, const bf16_t *v_lds, int 
 #pragma unroll
         for (int u = 0; u < 2; ++u)
             acc[dt + 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vg[dt][u], pf[u], acc[dt + 2], 0, 0, 0);
+    return true;
 }
 
 // QT: 32-row query tiles per wave.
 template <int QT>
 __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
-    __shared__ __attribute__((aligned(16))) bf16_t k_lds[2][32 * K_STRIDE];
-    __shared__ __attribute__((aligned(16))) bf16_t v_lds[2][HD * V_STRIDE];
+    constexpr int NBUF = 3, K_TILE = TILE, V_TILE = TILE;
+    __shared__ __attribute__((aligned(16))) bf16_t k_lds[NBUF][K_TILE];
+    __shared__ __attribute__((aligned(16))) bf16_t v_lds[NBUF][V_TILE];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // known to be uniform: scalar registers
     const int lq = lane & 31, lh = lane >> 5;
     int bx = blockIdx.x;
     const int chunk = bx % a.n_chunks;
@@ -226,84 +328,27 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
         l_run[i] = 0.f;
     }
 
-    // ---- K/V staging through buffer loads (an absent unit reads as zeros, no branch): per iteration each thread
-    // moves one 16-byte piece of K and of V^T for both units of the pair
     const size_t page_elems = (size_t)a.kv.n_kv * 16 * HD;
-    const __amdgpu_buffer_rsrc_t rk = attn_rsrc(a.kv.k_pages, (size_t)a.n_pages * page_elems * 2);
-    const __amdgpu_buffer_rsrc_t rv = attn_rsrc(a.kv.v_pages, (size_t)a.n_pages * page_elems * 2);
     const size_t scr_elems = (size_t)gridDim.x / a.n_chunks * (n_mt > 0 ? n_mt : 1) * 16 * HD;   // B * n_kv tiles
-    const __amdgpu_buffer_rsrc_t rks = attn_rsrc(a.k_scr, scr_elems * 2);
-    const __amdgpu_buffer_rsrc_t rvs = attn_rsrc(a.v_scr, scr_elems * 2);
-    bf16x8 st_k[2], st_v[2];
-    const int k_key = tid >> 4, k_piece = tid & 15;
-    const int v_d = tid >> 1, v_half = tid & 1;
-    const int k_in = (k_key * HD + k_piece * 8) * 2, v_in = (v_d * 16 + v_half * 8) * 2;   // byte offsets in a unit
     const int32_t *pt = a.kv.page_table + (size_t)(d.seq_base + b) * a.kv.pages_per_seq;
-    auto load_kv = [&](int n) {                         // n: position in this workgroup's iteration sequence
-        const int it = seq_it(n);
-        const bool live = n < n_seq;
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const int uu = 2 * it + u;
-            const bool in_cache = uu < n_cache_units, in_mask = !in_cache && uu < U && live;
-            int base = OOB, valid = 0;
-            if (in_cache && live) {                     // scalar (uniform) selects, no vector branch
-                const int page = pt[uu];
-                base = (int)((((size_t)page * a.kv.n_kv + g) * 16 * HD) * 2);
-                valid = min(16, L + d.nc - 16 * uu);
-            } else if (in_mask) {
-                const int mt = uu - n_cache_units;
-                base = (int)(((((size_t)b * a.kv.n_kv + g) * n_mt + mt) * 16 * HD) * 2);
-                valid = min(16, n_mask - 16 * mt);
-            }
-            const int ko = base == OOB ? OOB : base + k_in, vo = base == OOB ? OOB : base + v_in;
-            bf16x8 kk = in_mask ? attn_buf_load(rks, ko) : attn_buf_load(rk, ko);
-            bf16x8 vv = in_mask ? attn_buf_load(rvs, vo) : attn_buf_load(rv, vo);
-            if (valid < 16) {                           // uniform; slots past the data may hold anything
-#pragma unroll
-                for (int j = 0; j < 8; ++j)
-                    if (v_half * 8 + j >= valid) vv[j] = (bf16_t)0.f;
-            }
-            st_k[u] = kk;
-            st_v[u] = vv;
-        }
-    };
-    auto store_kv = [&](int buf) {
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            *(bf16x8 *)(&k_lds[buf][(16 * u + k_key) * K_STRIDE + k_piece * 8]) = st_k[u];
-            // V^T row layout: four-key groups g0..g7 of the pair stored as [g0 g2 | g1 g3 | g4 g6 | g5 g7]
-            typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
-            bf16x4 lo = {st_v[u][0], st_v[u][1], st_v[u][2], st_v[u][3]};
-            bf16x4 hi = {st_v[u][4], st_v[u][5], st_v[u][6], st_v[u][7]};
-            bf16_t *row = &v_lds[buf][v_d * V_STRIDE];
-            // this thread holds groups 2*half and 2*half+1 of unit u: half 0 -> positions 0 and 2, half 1 -> 1 and 3
-            *(bf16x4 *)(row + 4 * (4 * u + v_half)) = lo;
-            *(bf16x4 *)(row + 4 * (4 * u + 2 + v_half)) = hi;
-        }
-    };
 
-    load_kv(0);
-    store_kv(0);
-    __syncthreads();
-
-    for (int n = 0; n < n_seq; ++n) {
-        const int it = seq_it(n);
-        const int buf = n & 1;
-        load_kv(n + 1);
-
-        const bool pure = (2 * it + 1) < n_pure;
+    // one key-pair iteration of every query tile of this wave against LDS buffer `buf`
+    // (pure_c: both units lie wholly inside the prefix, no predicate.  The pure iterations are the leading ones of
+    // the sequence and get a loop of their own: with both forms in one loop body the compiler copied all 64
+    // accumulator registers back and forth at the point where the two paths meet, in every iteration.)
+    auto compute = [&](auto pure_c, int it, int buf) __attribute__((always_inline)) {
+        constexpr bool pure = decltype(pure_c)::value;
 #pragma unroll
         for (int i = 0; i < QT; ++i) {
             const int tile = t0 + wave + 4 * i;
             if (tile >= t1) continue;                       // wave-uniform
-            if (pure) {
-                attn_block<false>(k_lds[buf], v_lds[buf], lq, lh, qf[i], acc[i], m_run[i], l_run[i], a.scale_log2e,
-                                  0xffffu);
+            if constexpr (pure) {
+                attn_block<false>(k_lds[buf], v_lds[buf], lq, lh, qf[i], acc[i], m_run[i], l_run[i],
+                                       a.scale_log2e, 0xffffu);
             } else {
                 // A row sees a contiguous key range of each unit: cache positions below L + vis, or the mask rows
                 // of its own block.  The range becomes a 16-bit mask over the unit's keys, from which the lane
-                // picks its eight: register e of unit u <-> key 8*((e/4)%2) + 4*lh + e%4 of that unit.
+                // picks its eight: register e of unit u <-> key 8*lh + e%8 of that unit.
                 unsigned vis_bits = 0;                      // bit 8u+e: visible to this lane's query row
 #pragma unroll
                 for (int u = 0; u < 2; ++u) {
@@ -318,17 +363,173 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
                         const int hi = min(max(min((r_blk[i] + 1) * d.bl, n_mask) - m0, 0), 16);
                         m16 = (r_blk[i] >= 0 && hi > lo) ? (((1u << hi) - 1u) & ~((1u << lo) - 1u)) : 0u;
                     }
-                    const unsigned v8 = ((m16 >> (4 * lh)) & 0xfu) | (((m16 >> (8 + 4 * lh)) & 0xfu) << 4);
-                    vis_bits |= v8 << (8 * u);
+                    vis_bits |= ((m16 >> (8 * lh)) & 0xffu) << (8 * u);
                 }
                 if (!__any(vis_bits != 0)) continue;        // nothing of this pair is visible to this tile
-                attn_block<true>(k_lds[buf], v_lds[buf], lq, lh, qf[i], acc[i], m_run[i], l_run[i], a.scale_log2e,
-                                 vis_bits);
+                attn_block<true>(k_lds[buf], v_lds[buf], lq, lh, qf[i], acc[i], m_run[i], l_run[i],
+                                      a.scale_log2e, vis_bits);
             }
         }
+    };
 
-        store_kv(buf ^ 1);
-        __syncthreads();
+    const std::true_type pure_c;
+    const std::false_type masked_c;
+    // leading iterations whose two units lie wholly inside the prefix
+    const int n_fast = min(max(min(a1, n_pure >> 1) - a0, 0), nA);
+    {
+        // Direct loads: wave w moves unit w/2 of the pair: for K the LDS rows 8*(w%2) .. +7 of that unit (two
+        // instructions of 1 KiB: lane = (row, 16-byte slot), the slot holds piece slot ^ row%16 of the key the row
+        // stands for), for V^T the key half w%2 of all 128 d (lane = d).  The tiles land in buffer n % 3 two
+        // iterations ahead of their use; a wave waits for its own loads of iteration n (vmcnt), then the workgroup
+        // barrier makes all four waves' parts visible and at the same time frees the buffer of iteration n-1 for
+        // the loads of iteration n+2.
+        const int u_w = wave >> 1, half_w = wave & 1;
+        int k_voff[2], v_voff[2];
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) {
+            const int row = 8 * half_w + 4 * jj + (lane >> 4);                    // LDS row within the unit
+            const int key = (row & 3) | ((row & 4) << 1) | ((row & 8) >> 1);     // rows 4-7 <-> keys 8-11
+            k_voff[jj] = key * (HD * 2) + (((lane & 15) ^ row) << 4);
+            v_voff[jj] = (64 * jj + lane) * 32 + half_w * 16;
+        }
+        // An odd unit count leaves the second half of the last pair's tiles unwritten.  Its scores are masked by
+        // a select, so stale K bits do no harm, but its V^T is multiplied by probabilities of exactly zero and
+        // must not be NaN or Inf: the workgroup that runs that last pair clears the V^T tiles first.
+        if ((U & 1) && n_seq > 0 && seq_it(n_seq - 1) == n_it - 1) {
+            for (int i = tid; i < NBUF * V_TILE / 8; i += 256)
+                reinterpret_cast<bf16x8 *>(&v_lds[0][0])[i] = (bf16x8){0, 0, 0, 0, 0, 0, 0, 0};
+            __syncthreads();
+        }
+        // the Q fragments must have arrived before the loop: a wait for them inside it would be a vmcnt(0) and
+        // drain the tile loads in flight
+#pragma unroll
+        for (int i = 0; i < QT; ++i)
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+v"(qf[i][ks]));
+        const int4v dk = raw_desc(a.kv.k_pages, (size_t)a.n_pages * page_elems * 2);
+        const int4v dv = raw_desc(a.kv.v_pages, (size_t)a.n_pages * page_elems * 2);
+        const int4v dks = raw_desc(a.k_scr, scr_elems * 2), dvs = raw_desc(a.v_scr, scr_elems * 2);
+        typedef __attribute__((address_space(3))) unsigned char lds_byte;
+        const unsigned k_lds0 = (unsigned)(size_t)(lds_byte *)reinterpret_cast<unsigned char *>(&k_lds[0][0]);
+        const unsigned v_lds0 = (unsigned)(size_t)(lds_byte *)reinterpret_cast<unsigned char *>(&v_lds[0][0]);
+        // the page table does not change while the kernel runs: read through the constant address space, the page
+        // ids come by scalar loads (no vector-memory traffic that the vmcnt bookkeeping below would have to count)
+        const __attribute__((address_space(4))) int32_t *ptc = (const __attribute__((address_space(4))) int32_t *)pt;
+        // V^T slots past the data of a unit (the page the sequence ends in, the last mask tile) may hold anything:
+        // they are cleared in LDS before use (uniform, at most twice in a workgroup's life)
+        auto clear_tail = [&](int it, int buf) __attribute__((always_inline)) {
+            bool any = false;
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int uu = 2 * it + u;
+                int valid = 16;
+                if (uu < n_cache_units) valid = min(16, L + d.nc - 16 * uu);
+                else if (uu < U) valid = min(16, n_mask - 16 * (uu - n_cache_units));
+                if (valid < 16) {
+                    any = true;
+                    if (tid < 128) {
+#pragma unroll
+                        for (int h = 0; h < 2; ++h) {
+                            bf16x8 *pv = reinterpret_cast<bf16x8 *>(&v_lds[buf][0]) + (u * 2 + h) * 128 + tid;
+                            bf16x8 vv = *pv;
+#pragma unroll
+                            for (int j = 0; j < 8; ++j)
+                                if (8 * h + j >= valid) vv[j] = (bf16_t)0.f;
+                            *pv = vv;
+                        }
+                    }
+                }
+            }
+            if (any) lds_barrier();
+        };
+        auto unit_of = [&](int m) { return 2 * seq_it(m) + u_w; };
+        auto page_of = [&](int m) {                          // page id of this wave's unit in iteration m (or 0)
+            const int uu = unit_of(m);
+            return (m < n_seq && uu < n_cache_units) ? ptc[uu] : 0;
+        };
+        int b_cur = 0, b_nxt = 1, b_far = 2;                // buffers of iterations n, n+1, n+2
+        int c_nxt = 0;                                      // loads this wave issued last (0 or 4)
+        int page = page_of(0);                              // page id of the next loads to be issued
+        auto issue = [&](int m, int buf) __attribute__((always_inline)) {      // this wave's loads of iteration m
+            const int uu = unit_of(m);
+            c_nxt = 0;
+            if (m < n_seq && uu < U) {
+                const unsigned kd = k_lds0 + buf * (K_TILE * 2) + (u_w * 16 + 8 * half_w) * 256;
+                const unsigned vd = v_lds0 + buf * (V_TILE * 2) + (u_w * 2 + half_w) * 2048;
+                if (uu < n_cache_units) {
+                    const int base = (int)((((size_t)page * a.kv.n_kv + g) * 16 * HD) * 2);
+#pragma unroll
+                    for (int jj = 0; jj < 2; ++jj) {
+                        dma16(kd + 1024 * jj, k_voff[jj], dk, base);
+                        dma16(vd + 1024 * jj, v_voff[jj], dv, base);
+                    }
+                } else {
+                    const int mt = uu - n_cache_units;
+                    const int base = (int)(((((size_t)b * a.kv.n_kv + g) * n_mt + mt) * 16 * HD) * 2);
+#pragma unroll
+                    for (int jj = 0; jj < 2; ++jj) {
+                        dma16(kd + 1024 * jj, k_voff[jj], dks, base);
+                        dma16(vd + 1024 * jj, v_voff[jj], dvs, base);
+                    }
+                }
+                c_nxt = 4;
+            }
+            page = page_of(m + 1);
+        };
+        // make the tiles of iteration n usable and start the loads of iteration n+2 into the buffer that the
+        // barrier has just freed (every wave is past iteration n-1).  A wave's loads of iteration n have landed
+        // once no more than those of n+1, its latest, are in flight.
+        auto ready = [&](int n) __attribute__((always_inline)) {
+            if (c_nxt == 4) __builtin_amdgcn_s_waitcnt(4 | (7 << 4) | (15 << 8));
+            else __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8));
+            lds_barrier();
+            issue(n + 2, b_far);
+        };
+        auto rotate = [&]() __attribute__((always_inline)) {
+            const int t = b_cur;
+            b_cur = b_nxt;
+            b_nxt = b_far;
+            b_far = t;
+        };
+        auto general = [&](int n) __attribute__((always_inline)) {
+            const int it = seq_it(n);
+            clear_tail(it, b_cur);
+            compute(masked_c, it, b_cur);
+        };
+        issue(0, b_cur);
+        issue(1, b_nxt);
+        int n = 0;
+        if (n_seq > 0) {
+            ready(0);
+            // the first iteration moves the references off -inf; the iterations that follow, while both their
+            // units lie inside the prefix, keep them where they are (no rescale arm in that loop); a wave whose
+            // scores outgrow its reference by 2^60 leaves for the general loop (the waves of a workgroup may
+            // be in different loops: each iteration of either passes the same one barrier)
+            if (n_fast > 0) compute(pure_c, seq_it(0), b_cur);
+            else general(0);
+            for (n = 1; n < n_fast; ++n) {
+                rotate();
+                ready(n);
+                bool ok = true;
+#pragma unroll
+                for (int i = 0; i < QT; ++i) {
+                    const int tile = t0 + wave + 4 * i;
+                    if (tile < t1)
+                        ok = ok && attn_block_fixed_ref(k_lds[b_cur], v_lds[b_cur], lq, lh, qf[i], acc[i], m_run[i],
+                                                             l_run[i], a.scale_log2e);
+                }
+                if (!ok) break;
+            }
+            if (n < n_fast) {          // refused: this iteration's tiles are ready, only the block has to run
+                general(n);
+                ++n;
+            }
+            for (; n < n_seq; ++n) {
+                rotate();
+                ready(n);
+                general(n);
+            }
+        }
     }
 
     // ---- a single split is the whole answer: normalise in registers and store it (a lane holds, for its query
