@@ -18,10 +18,11 @@
 // padding), rows 4-7 and 8-11 of a unit exchanged so that a lane's score registers of a unit are eight consecutive
 // keys, the same eight that one 16-byte piece of V^T holds.
 //
-// Softmax numerators are taken against an integral power-of-two reference (ceil of the running maximum in
-// log2 units): their bf16 rounding is then independent of the reference in force, i.e. of tiling and splits, and
-// every rescale is exact.  While the keys are plain prefix keys the reference is not even moved (see
-// attn_block_fixed_ref): the loop then has no rescale arm at all.
+// Softmax numerators are taken against an integral power-of-two reference (ceil of a running maximum in log2
+// units): their bf16 rounding is then independent of the reference in force, i.e. of tiling and splits, and
+// every rescale is exact.  The reference is lazy: a row's reference is set by its first visible block and moves
+// only when the scores outgrow it by 2^60, which in practice is never; the loop over plain prefix keys therefore
+// has no rescale arm at all (attn_block_fixed_ref), and leaves for the general loop if that ever happens.
 //
 // Keys come in units of 16: cache pages 0 .. ceil((L+nc)/16)-1, then the mask rows' scratch tiles.  Pages that
 // lie wholly below L need no mask at all (every row sees the whole prefix); everything else goes through the
@@ -120,7 +121,12 @@ __device__ inline void attn_block(const bf16_t *k_lds, const bf16_t *v_lds, int 
         mx = fmaxf(mx, s[e]);
     }
     mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m_new = fmaxf(m_run, ceilf(mx * c));
+    // The reference of a row moves only when its scores outgrow it by 2^60 (or it is still -inf): the same rule
+    // that makes attn_block_fixed_ref refuse a block, so that which of the two ran a block (that depends on how
+    // much of the key range is plain prefix, i.e. on the sequence length) leaves no trace in the result.  (The
+    // numerators' mantissas do not depend on the reference in exact arithmetic, but fma(s, c, -m) is rounded.)
+    const bool grow = !(mx * c <= m_run + 60.f);
+    const float m_new = grow ? fmaxf(m_run, ceilf(mx * c)) : m_run;
     const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
     const bf16x2 ones = {(bf16_t)1.0f, (bf16_t)1.0f};
     float psum = 0.f;
@@ -168,12 +174,12 @@ __device__ inline void attn_block(const bf16_t *k_lds, const bf16_t *v_lds, int 
     }
 }
 
-// The same block for keys that are all visible, against a reference that is *not* moved: the numerators are
+// The same block for keys that are all visible, without the arm that moves the reference: the numerators are
 // 2^(s.c - m_run) with the reference of an earlier block, so they may exceed 1 (by less than 2^60, or the block
-// is refused: the caller then runs attn_block, which moves the reference).  bf16 rounding is a matter of the
-// mantissa alone, and every quantity (numerators, denominator, O^T) carries the same power of two, so the
-// normalised result is bit for bit that of the moving reference.  No rescale arm means no branch that rejoins
-// around the accumulators: with one, the compiler copied all 64 accumulator registers twice per block.
+// is refused before it changes anything: the caller then runs attn_block, which moves the reference by the same
+// rule).  bf16 rounding is a matter of the mantissa alone, and every quantity (numerators, denominator, O^T)
+// carries the same power of two.  No rescale arm means no branch that rejoins around the accumulators: with one,
+// the compiler copied all 64 accumulator registers twice per block.
 __device__ inline bool attn_block_fixed_ref(const bf16_t *k_lds, const bf16_t *v_lds, int lq, int lh,
                                             const bf16x8 (&qf)[8], f32x16 (&acc)[4], float m_run, float &l_run,
                                             float c) {

@@ -175,3 +175,46 @@ def test_hybrid_attention_bf16_microbench_shape(T):
 def test_hybrid_attention_fp32(T, k, L):
     for got, want in _attention_case(T, TI.TINY, 2, [L, max(L - 3, 0)], k, k, k, 1, seed=k + L, dtype_id=T.TIDAR_F32):
         assert torch.allclose(got, want, atol=2e-5), float((got - want).abs().max())
+
+
+@pytest.mark.parametrize("L1,L2,nc", [(990, 968, 40), (290, 260, 48), (4100, 4070, 272), (2050, 2000, 272)])
+def test_attention_row_does_not_depend_on_how_much_of_its_context_is_cached(T, L1, L2, nc):
+    """The same query over the same keys in two calls of the same shape (nc new causal rows, one bound on the key
+    count), once after L1 cached keys, once after L2 < L1: the rows at positions [L1, L2 + nc) appear in both, with
+    the same context, and their outputs must be the same bits.  Between L2 and L1 lie key pages that are plain
+    prefix in one call (the kernel's loop without predicate and without a rescale arm) and predicated pages in the
+    other; the key splits are the same (same bound, same row count), and the softmax reference of a row moves by a
+    rule that looks at its keys alone, so nothing of that difference may show.  8B-shape heads (32 query / 8 kv
+    heads); the scores are N(0, 16), so that a row's running maximum keeps moving over thousands of keys."""
+    sh = TI.SHAPE_8B.with_layers(1)
+    n_q, n_kv, hd = sh.n_q_heads, sh.n_kv_heads, sh.head_dim
+    tdt = torch.bfloat16
+    ctx = T.tidar_create(T.make_config(sh, T.TIDAR_BF16, max_k=16, max_batch=1))
+    total = L1 + nc
+    pps = (total + 15) // 16 + 1
+    table = TI.shuffled_page_table(pps, pps + 3, seed=total).view(1, pps)
+    K = TI.make_normal((total, n_kv, hd), total + 1, tdt)
+    V = TI.make_normal((total, n_kv, hd), total + 2, tdt)
+    Q = TI.make_normal((total, n_q, hd), total + 3, tdt, std=4.0)       # scores ~ N(0, 4^2): the running maximum keeps growing
+    ws = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
+    outs = {}
+    for L in (L1, L2):
+        print(f"attention rows at {L}..{L + nc - 1}", flush=True)
+        kp = torch.zeros((1, pps + 3, n_kv, 16, hd), dtype=tdt)
+        vp = torch.zeros((1, pps + 3, n_kv, hd, 16), dtype=tdt)
+        for p in range(L):
+            kp[0, table[0, p // 16], :, p % 16, :] = K[p]
+            vp[0, table[0, p // 16], :, :, p % 16] = V[p]
+        kpd, vpd, tabd = kp.cuda(), vp.cuda(), table.cuda().contiguous()
+        kv = T.tidar_kv_cache(kpd.data_ptr(), vpd.data_ptr(), tabd.data_ptr(), pps, pps + 3)
+        out = torch.empty((1, nc, n_q, hd), dtype=tdt, device="cuda")
+        plen = torch.tensor([L], dtype=torch.int32, device="cuda")
+        sl = slice(L, L + nc)
+        T.tidar_hybrid_attention(ctx, kv, 0, 1, plen, Q[sl].cuda().contiguous()[None], K[sl].cuda().contiguous()[None],
+                                 V[sl].cuda().contiguous()[None], nc, 0, 1, 1, out, L1, ws)
+        torch.cuda.synchronize()
+        outs[L] = out[0].cpu()
+    a, b = outs[L1][: L2 + nc - L1], outs[L2][L1 - L2:]
+    assert a.shape[0] >= 8 and not torch.isnan(a.float()).any()
+    assert torch.equal(a, b), float((a.float() - b.float()).abs().max())
+    T.tidar_destroy(ctx)

@@ -329,14 +329,17 @@ def test_small_bf16_long_prompt_two_default_passes(T):
     eng.close()
 
 
-def test_bf16_logits_do_not_depend_on_the_acceptance_history(T, small):
+@pytest.mark.parametrize("k,P", [(8, 200), (8, 203), (16, 900)])
+def test_bf16_logits_do_not_depend_on_the_acceptance_history(T, small, k, P):
     """With one length bound held over the run, a causal row's logits depend on its context alone, bit for bit: the
-    GEMMs group a row's sums the same way whatever rows travel with it, and the attention splits are cut by key
-    position.  Reference: steps that each accept one token (the row is c_0 at its position).  Then the same
-    positions again as rows c_0..c_{k-1} of ONE step whose drafts are the reference tokens."""
+    GEMMs group a row's sums the same way whatever rows travel with it, the attention splits are cut by key
+    position, and the softmax reference of a row moves by a rule that looks at its keys alone.  Reference: steps
+    that each accept one token (the row is c_0 at its position).  Then the same positions again as rows
+    c_0..c_{k-1} of ONE step whose drafts are the reference tokens.  (203 and 900: the prefix lengths of the run
+    straddle a multiple of 16, so a key page is plain prefix, handled by the attention kernel's loop without a
+    rescale arm, for some of the steps and a masked page for the others; 900: dozens of such pages per split.)"""
     eng, _ = small
     sh = TI.SMALL_GQA
-    k, P = 8, 200
     hint = P + 4 * k
     prompt = TI.make_prompt(sh, P, seed=123)
     first, _ = eng.prefill(prompt, k)
