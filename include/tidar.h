@@ -91,7 +91,10 @@ typedef struct {
  * Token position p of sequence b lives in page page_table[b][p/16], slot p%16.
  * After a step, positions < prefix_len[b] hold exact causal K/V; anything at or
  * beyond prefix_len[b] is unspecified (rejected drafts are evicted by not
- * advancing prefix_len over them).
+ * advancing prefix_len over them).  One layer's K (or V) pages may not exceed 2 GiB
+ * (n_pages * n_kv_heads * 16 * head_dim * element size <= 0x7fffffe0: the kernels use
+ * 32-bit byte offsets); larger caches are rejected with TIDAR_EINVAL.  The pages need not
+ * be initialised: slots that hold no committed token are never read as data.
  */
 typedef struct {
     void *k_pages;

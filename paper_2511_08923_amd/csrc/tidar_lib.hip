@@ -165,8 +165,12 @@ bool weights_ok(const tidar_weights *w) {
            w->w_gate_up && w->w_down;
 }
 
-bool kv_ok(const tidar_kv_cache *kv) {
-    return kv && kv->k_pages && kv->v_pages && kv->page_table && kv->pages_per_seq > 0 && kv->n_pages > 0;
+// The kernels address a layer's pages with 32-bit byte offsets (raw buffer loads): a layer's K (or V) pages may
+// not exceed 2 GiB, i.e. 65 535 pages of the 8B shape = one million tokens per layer buffer.
+bool kv_ok(const tidar_config &c, const tidar_kv_cache *kv) {
+    if (!(kv && kv->k_pages && kv->v_pages && kv->page_table && kv->pages_per_seq > 0 && kv->n_pages > 0))
+        return false;
+    return (int64_t)kv->n_pages * c.n_kv_heads * 16 * c.head_dim * (int64_t)esize(c.dtype) <= 0x7fffffe0ll;
 }
 
 KvView layer_view(const tidar_config &c, const tidar_kv_cache *kv, int layer) {
@@ -478,7 +482,7 @@ tidar_status tidar_step(tidar_ctx *ctx, const tidar_weights *w, const tidar_kv_c
                         int32_t *prefix_len, const int32_t *drafts, int32_t k, const tidar_mode *mode,
                         int32_t *accepted_len, int32_t *accepted_tokens, int32_t *next_drafts, float *logits_out,
                         int32_t max_prefix_len_hint, void *ws, size_t ws_bytes, void *stream) {
-    if (!ctx || !weights_ok(w) || !kv_ok(kv) || !prefix_len || !drafts || !mode_ok(mode) || !accepted_len ||
+    if (!ctx || !weights_ok(w) || !kv_ok(ctx->cfg, kv) || !prefix_len || !drafts || !mode_ok(mode) || !accepted_len ||
         !accepted_tokens || !next_drafts || !ws)
         return TIDAR_EINVAL;
     const tidar_config &c = ctx->cfg;
@@ -502,7 +506,7 @@ tidar_status tidar_step(tidar_ctx *ctx, const tidar_weights *w, const tidar_kv_c
 tidar_status tidar_ar_step(tidar_ctx *ctx, const tidar_weights *w, const tidar_kv_cache *kv, int32_t batch,
                            int32_t *prefix_len, const int32_t *token_in, const tidar_mode *mode, int32_t *token_out,
                            float *logits_out, int32_t max_prefix_len_hint, void *ws, size_t ws_bytes, void *stream) {
-    if (!ctx || !weights_ok(w) || !kv_ok(kv) || !prefix_len || !token_in || !mode_ok(mode) || !token_out || !ws)
+    if (!ctx || !weights_ok(w) || !kv_ok(ctx->cfg, kv) || !prefix_len || !token_in || !mode_ok(mode) || !token_out || !ws)
         return TIDAR_EINVAL;
     const tidar_config &c = ctx->cfg;
     if (batch < 1 || batch > c.max_batch || max_prefix_len_hint < 0) return TIDAR_EINVAL;
@@ -526,7 +530,7 @@ tidar_status tidar_prefill(tidar_ctx *ctx, const tidar_weights *w, const tidar_k
                            const int32_t *prompt, int32_t prompt_stride, const int32_t *prompt_len, int32_t k,
                            const tidar_mode *mode, int32_t *prefix_len, int32_t *first_drafts, float *logits_out,
                            void *ws, size_t ws_bytes, void *stream) {
-    if (!ctx || !weights_ok(w) || !kv_ok(kv) || !prompt || !prompt_len || !mode_ok(mode) || !prefix_len ||
+    if (!ctx || !weights_ok(w) || !kv_ok(ctx->cfg, kv) || !prompt || !prompt_len || !mode_ok(mode) || !prefix_len ||
         !first_drafts || !ws)
         return TIDAR_EINVAL;
     const tidar_config &c = ctx->cfg;
@@ -591,7 +595,7 @@ tidar_status tidar_score(tidar_ctx *ctx, const tidar_weights *w, const tidar_kv_
                          const int32_t *tokens, int32_t stride, const int32_t *len, int32_t block_len, float alpha,
                          float *ar_logprob, float *diff_logprob, float *loss, void *ws, size_t ws_bytes,
                          void *stream) {
-    if (!ctx || !weights_ok(w) || !kv_ok(kv) || !tokens || !len || !ar_logprob || !ws) return TIDAR_EINVAL;
+    if (!ctx || !weights_ok(w) || !kv_ok(ctx->cfg, kv) || !tokens || !len || !ar_logprob || !ws) return TIDAR_EINVAL;
     const tidar_config &c = ctx->cfg;
     if (batch < 1 || batch > c.max_batch || stride < 1 || block_len < 0 || block_len > TIDAR_MAX_K)
         return TIDAR_EINVAL;
@@ -643,7 +647,7 @@ tidar_status tidar_hybrid_attention(tidar_ctx *ctx, const tidar_kv_cache *kv, in
                                     const int32_t *prefix_len, const void *q, const void *k_new, const void *v_new,
                                     int32_t n_causal, int32_t n_blocks, int32_t block_len, int32_t cond0, void *out,
                                     int32_t max_prefix_len_hint, void *ws, size_t ws_bytes, void *stream) {
-    if (!ctx || !kv_ok(kv) || !prefix_len || !q || !k_new || !v_new || !out || !ws) return TIDAR_EINVAL;
+    if (!ctx || !kv_ok(ctx->cfg, kv) || !prefix_len || !q || !k_new || !v_new || !out || !ws) return TIDAR_EINVAL;
     const tidar_config &c = ctx->cfg;
     if (layer < 0 || layer >= c.n_layers || batch < 1 || batch > c.max_batch) return TIDAR_EINVAL;
     if (n_causal < 1 || n_blocks < 0 || block_len < 1 || block_len > TIDAR_MAX_K || cond0 < 0 ||

@@ -87,6 +87,10 @@ def test_step_rejects_null_and_capacity_before_any_launch(T):
     bad = T.make_mode(sample=True, temperature=0.0)
     rc = T._lib.tidar_step(ctx, C.byref(w), C.byref(kv), 1, 8, 8, 4, C.byref(bad), 8, 8, 8, None, 8, 8, 1 << 30, None)
     assert rc == 1
+    # a layer's pages beyond 2 GiB cannot be addressed with 32-bit offsets: 4 heads x 16 x 32 x 4 B = 8 KiB per page
+    huge = T.tidar_kv_cache(8, 8, 8, 2, (1 << 31) // 8192)
+    rc = T._lib.tidar_step(ctx, C.byref(w), C.byref(huge), 1, 8, 8, 4, C.byref(mode), 8, 8, 8, None, 8, 8, 1 << 30, None)
+    assert rc == 1
     T.tidar_destroy(ctx)
 
 
