@@ -218,3 +218,15 @@ def test_attention_row_does_not_depend_on_how_much_of_its_context_is_cached(T, L
     assert a.shape[0] >= 8 and not torch.isnan(a.float()).any()
     assert torch.equal(a, b), float((a.float() - b.float()).abs().max())
     T.tidar_destroy(ctx)
+
+
+def test_hybrid_attention_bf16_every_prefix_length_mod_32(T):
+    """The tile pipeline's edge cases in one sweep: prefix lengths 0..70 (every offset inside a key pair, an odd and
+    an even number of key units, sequences that end in a partly filled page, workgroups with one or two iterations,
+    splits that come out empty) for the decode shapes k = 4 and k = 16; cache pages start out as NaN."""
+    for k in (4, 16):
+        for L in list(range(0, 36)) + list(range(60, 71)):
+            for got, want in _attention_case(T, TI.SMALL_GQA, 1, [L], k, k, k, 1, seed=1000 * k + L,
+                                             dtype_id=T.TIDAR_BF16):
+                assert not torch.isnan(got).any(), (k, L)
+                assert torch.allclose(got, want, atol=1e-2, rtol=2e-2), (k, L, float((got - want).abs().max()))
