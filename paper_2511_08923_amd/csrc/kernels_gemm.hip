@@ -507,7 +507,8 @@ void launch_large(const bf16_t *a, const bf16_t *w, float *out, int M, int N, in
     const int n_colblk = grid.x, n_pass = grid.z;
     int swz_p = 0, swz_c = 0;
     if (p.swz > 0 && n_pass >= 2) {          // super-tiles of swz x swz workgroups, dealt to the XCDs in turn
-        swz_p = swz_c = p.swz;
+        swz_p = p.swz < n_pass ? p.swz : n_pass;
+        swz_c = p.swz;
         const int n_st = ((n_pass + swz_p - 1) / swz_p) * ((n_colblk + swz_c - 1) / swz_c);
         grid = dim3(8 * ((n_st + 7) / 8) * swz_p * swz_c, p.splits, 1);
     }
@@ -558,12 +559,21 @@ GemmPlan plan_gemm_bf16(int M, int N, int K, bool force_single_split) {
         // many column blocks, one split, more than five row tiles: 256-column workgroups over five row tiles
         // (four waves side by side, no weight fragment loaded twice) in two or more row passes.  Only when the
         // whole grid is resident at once: the passes of a column block then run together and the second read
-        // of its weights hits L2 (measured on the LM head, whose grid takes several rounds: 30 % slower)
+        // of its weights hits L2 (measured on the LM head, whose grid takes several rounds: 30 % slower in
+        // plain launch order)
         const int wide_wgs = ((N + 255) / 256) * ((t + 4) / 5);
         if (splits == 1 && wgs >= 128 && t > 5 && wide_wgs <= 256) {
             p.wide = 1;
             p.mt = 5;
             ctl = 5;
+        } else if (splits == 1 && wgs >= 512 && t > 5) {
+            // The LM head: its grid takes several rounds either way.  With the (row pass, column block) plane
+            // dealt to the XCDs in super-tiles the passes of a column block run on one XCD at about the same
+            // time and share the weights through its L2: 436 -> 402 us at 272 rows.
+            p.wide = 1;
+            p.mt = 5;
+            ctl = 5;
+            p.swz = 4;
         }
         // 512 rows and more: the launch is bound by the compute units' L1 bandwidth, not by HBM (every workgroup
         // pulls its A rows and W columns through it), so the workgroup tile is made as square as the register
