@@ -12,8 +12,9 @@
  *     "host" pointers are ordinary host addresses.  All tensor memory is owned
  *     by the caller; the library allocates no device memory and keeps no
  *     pointer after a call returns.
- *   - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the
- *     null stream) and the call returns without synchronising.
+ *   - Work is enqueued on `stream` (a hipStream_t of the current device passed
+ *     as void*, NULL = the null stream) and the call returns without
+ *     synchronising.
  *   - Argument and capacity errors are found on the host before anything is
  *     enqueued; a failing call has no effect on device memory.
  *   - dtype 1 (bf16): activations, Q/K/V and weights are bf16, the residual

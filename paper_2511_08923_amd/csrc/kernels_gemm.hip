@@ -513,11 +513,14 @@ void launch_large(const bf16_t *a, const bf16_t *w, float *out, int M, int N, in
         grid = dim3(8 * ((n_st + 7) / 8) * swz_p * swz_c, p.splits, 1);
     }
     constexpr size_t SMEM = (size_t)2 * CTL * 8 * 1024;
-    static bool attr_set = false;          // LDS above 64 KiB has to be granted per kernel
-    if (!attr_set) {
+    // LDS above 64 KiB has to be granted per kernel, on every device the kernel is launched on
+    static bool attr_set[64] = {};
+    int dev = 0;
+    (void)hipGetDevice(&dev);
+    if (dev < 0 || dev >= 64 || !attr_set[dev]) {
         (void)hipFuncSetAttribute((const void *)gemm_bf16_large_kernel<MTA, WIDE>,
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)SMEM);
-        attr_set = true;
+        if (dev >= 0 && dev < 64) attr_set[dev] = true;
     }
     gemm_bf16_large_kernel<MTA, WIDE><<<grid, 256, SMEM, st>>>(a, w, out, M, N, K, p.splits, epi, swz_p, swz_c, n_pass,
                                                                n_colblk);
