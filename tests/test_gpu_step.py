@@ -367,6 +367,62 @@ def test_bf16_logits_do_not_depend_on_the_acceptance_history(T, small, k, P):
     assert int(a[0]) == k                             # every draft was the reference token: all accepted
 
 
+def test_bf16_step_replayed_from_a_hip_graph_equals_host_launches(T, small):
+    """The step enqueues kernels only (no memset or copy nodes), so it can be captured once and replayed: every
+    replay must give the bits of the same step launched from the host.  Replays are interleaved with host-launched
+    steps and synchronisations, and go back and forth between two states (prefix length and drafts are read from
+    device buffers at replay time; the length bound is the captured one)."""
+    eng, _ = small
+    sh = TI.SMALL_GQA
+    k, P = 8, 150
+    hint = P + 4 * k
+    prompt = TI.make_prompt(sh, P, seed=91)
+    first, _ = eng.prefill(prompt, k)
+    d0 = first.clone()
+    a1, acc1, nxt1, _ = eng.step(d0, k, hint=hint)                       # host launches, state 0 -> state 1
+    torch.cuda.synchronize()
+    P1 = int(eng.prefix_len[0])
+    assert P1 == P + int(a1[0])
+    d1 = nxt1.clone()
+    a2, acc2, nxt2, _ = eng.step(d1, k, hint=hint)                       # state 1 -> state 2
+    torch.cuda.synchronize()
+    want = {0: (a1.clone(), acc1.clone(), nxt1.clone()), 1: (a2.clone(), acc2.clone(), nxt2.clone())}
+
+    drafts = torch.empty_like(d0)
+    out = (torch.empty(1, dtype=torch.int32, device="cuda"), torch.empty(1, k, dtype=torch.int32, device="cuda"),
+           torch.empty(1, k, dtype=torch.int32, device="cuda"))
+    drafts.copy_(d0)
+    eng.prefix_len[:1].fill_(P)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        eng.step(drafts, k, hint=hint, out=out)                          # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    eng.prefix_len[:1].fill_(P)
+    with torch.cuda.graph(g):
+        eng.step(drafts, k, hint=hint, out=out)
+    for rep, state in enumerate([0, 1, 0, 0, 1]):
+        drafts.copy_(d0 if state == 0 else d1)
+        eng.prefix_len[:1].fill_(P if state == 0 else P1)
+        for o in out:
+            o.fill_(-7)
+        g.replay()
+        torch.cuda.synchronize()
+        a, acc, nxt = want[state]
+        n = int(a[0])
+        assert torch.equal(out[0], a), (rep, state)
+        assert torch.equal(out[1][0, :n], acc[0, :n]), (rep, state)
+        assert torch.equal(out[2], nxt), (rep, state)
+        assert int(eng.prefix_len[0]) == (P if state == 0 else P1) + n
+        # host-launched work between the replays
+        eng.prefix_len[:1].fill_(P)
+        b = eng.step(d0, k, hint=hint)
+        torch.cuda.synchronize()
+        assert torch.equal(b[0], a1) and torch.equal(b[2], nxt1)
+
+
 def test_small_bf16_device_tidar_vs_device_ar(T, small):
     """On-device check 3 in bf16: streams agree until a row whose top-2 margin is within rounding."""
     eng, model = small
