@@ -258,7 +258,7 @@ tidar_status tidar_score(tidar_ctx *ctx, const tidar_weights *w, const tidar_kv_
                          void *stream);
 
 /* Causal rows per prefill pass (the prompt is prefilled in causal chunks through the step's kernels, the mask block
- * of Appendix B joins the last chunk).  Default 1024; 1..4096.  Larger passes stream the weights fewer times and
+ * of Appendix B joins the last chunk).  Default 2048; 1..4096.  Larger passes stream the weights fewer times and
  * need a larger workspace: call before tidar_workspace_bytes / tidar_score_workspace_bytes.  Host only. */
 tidar_status tidar_set_prefill_chunk(tidar_ctx *ctx, int32_t rows);
 

@@ -589,13 +589,32 @@ GemmPlan plan_gemm_bf16(int M, int N, int K, bool force_single_split) {
             const int passes = (t + 7) / 8;
             p.mt = ctl = (t + passes - 1) / passes;      // 6, 7 or 8 row tiles per pass: the passes come out even
             p.swz = (N + 255) / 256 >= 256 ? 4 : 0;
+            // With this many rows the row passes fill the chip by themselves, and a split costs M x N floats
+            // written and read again (570 MB per launch at 8704 rows and N = 4096, four splits).  The count, never
+            // above the (N, K) rule's, minimises an estimate in microseconds: rounds of 256 workgroups x (a
+            // workgroup's share of K at the measured 22 ns per k of a 256 x 256 tile + 8 of prologue and
+            // epilogue) + the partial sums through the fabric at 6 TB/s out and 4 TB/s back in.  It is a function
+            // of the pass count (rows / 256, rounded up) alone, so within this class a row's sum is grouped the
+            // same way for every row count with the same number of passes.
+            const int base = ((N + 255) / 256) * passes, s_max = splits;
+            double best = 0.0;
+            for (int c = 1; c <= s_max; ++c) {
+                const int sc = fit(c);
+                const int rounds = (base * sc + 255) / 256;
+                const double cost = rounds * (0.022 * K / sc + 8.0) + sc * (256.0 * passes) * N * 1.67e-6;
+                if (c == 1 || cost < best) {
+                    best = cost;
+                    splits = sc;
+                }
+            }
         }
         p.m_chunks = (t + ctl - 1) / ctl;
     }
-    if (const char *e = getenv("TIDAR_GEMM_SPLITS")) {   // tuning override for sweeps (unset in normal use)
-        int v = atoi(e);
-        if (v >= 1 && !force_single_split) splits = fit(v);
-    }
+    static const int env_splits = [] {                   // tuning override for sweeps (unset in normal use)
+        const char *e = getenv("TIDAR_GEMM_SPLITS");
+        return e ? atoi(e) : 0;
+    }();
+    if (env_splits >= 1 && !force_single_split) splits = fit(env_splits);
     p.splits = splits;
     return p;
 }

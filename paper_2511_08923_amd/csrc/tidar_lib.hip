@@ -36,7 +36,7 @@ namespace {
 // Causal rows per prefill pass unless the caller sets another count: measured on the 8B shape, a 4096-token prompt
 // takes 117 ms in passes of 256 rows, 93 ms in passes of 1024 and 92 ms in passes of 2048 (every pass streams all
 // weights once, so fewer and larger passes win until the GEMMs are compute-bound).
-constexpr int kDefaultPrefillChunk = 1024;
+constexpr int kDefaultPrefillChunk = 2048;
 constexpr int kMaxPrefillChunk = 4096;
 
 struct Prof {
@@ -70,16 +70,19 @@ struct Layout {
 
 size_t gemm_out_floats(const tidar_config &c, int M, int N, int K) {
     if (c.dtype != TIDAR_BF16) return pt_split_stride(M, N);
-    // the split count depends on the row-tile class of M; taking the maximum over the class boundaries
-    // below M keeps the size monotone in M
-    const int bounds[5] = {16, 32, 80, 144, M};
+    // the split count depends on the row-tile class of M (and, from 481 rows on, on the number of 256-row passes);
+    // taking the maximum over the class boundaries below M keeps the size monotone in M and large enough for
+    // every call with fewer rows (the passes of a prefill differ in length)
     size_t best = 0;
-    for (int i = 0; i < 5; ++i) {
-        int m = bounds[i] < M ? bounds[i] : M;
+    auto consider = [&](int m) {
+        m = m < M ? m : M;
         GemmPlan p = plan_gemm_bf16(m, N, K, false);
         size_t v = (size_t)p.splits * pt_split_stride(m, N);
         if (v > best) best = v;
-    }
+    };
+    const int bounds[5] = {16, 32, 80, 144, M};
+    for (int i = 0; i < 5; ++i) consider(bounds[i]);
+    for (int m = 512; m < M; m += 256) consider(m);      // the largest row count of each pass count
     return best;
 }
 
