@@ -20,9 +20,9 @@
 //     64-column groups) or, for single-split grids that are resident all at once, side by side over 256 columns
 //     (no weight fragment is then loaded by two waves).  The weight fragment is the MFMA's first operand, so the
 //     accumulators hold the output transposed (lane = row): every epilogue starts from that.
-//   * split-K over blockIdx.y works in units of 512 k, row passes over blockIdx.z; the split count depends on
-//     (N, K) and the kernel class (M <= 32 or not) only, so the partial-sum grouping of a row never depends on
-//     how many rows travel with it.  Splits fill about half the CUs, two row passes the other half: a split
+//   * split-K over blockIdx.y works in units of 512 k, row passes over blockIdx.z; up to 480 rows the split count
+//     depends on (N, K) and the kernel class (M <= 32 or not) only, so the partial-sum grouping of a row does not
+//     depend on how many rows travel with it (from 481 rows on it also follows the number of 256-row passes).  Splits fill about half the CUs, two row passes the other half: a split
 //     costs an M x N partial sum written and read again, a row pass only a second read of W from L2.
 //   * output: [split][32-column tile][row][32] fp32 partial sums (summed in fixed order by the consumer), or
 //     row-major logits, or - fused epilogues - bf16 SwiGLU products in the next GEMM's A-fragment layout, or
