@@ -53,7 +53,10 @@ def _gemm(T, ctx, a, w):
                                    (512, 1024, 1024), (1000, 4096, 4096), (1025, 784, 608), (2176, 1536, 12288),
                                    (600, 16400, 384), (777, 65536 + 48, 256),
                                    # six row tiles per pass (17 tiles as 6+6+5, 18 as 6+6+6)
-                                   (544, 2048, 1024), (576, 6144, 512)])
+                                   (544, 2048, 1024), (576, 6144, 512),
+                                   # many rows: the split count follows the number of 256-row passes (3, 2 and 1
+                                   # splits where up to 1024 rows take 4)
+                                   (1280, 4096, 4096), (1536, 4096, 2048), (2176, 4096, 4096)])
 def test_gemm_matches_oracle_matmul(T, ctx8b, M, N, K):
     print(f"gemm M={M} N={N} K={K}", flush=True)
     a = TI.make_normal((M, K), seed=M * 7 + K, dtype=torch.bfloat16)
