@@ -307,6 +307,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
     // ---- this wave's query tiles: Q fragments (B operand: lane = (q row, hd half of the k step)), row info
     bf16x8 qf[QT][8];
     int r_vis[QT], r_blk[QT];
+    int vis_min = 0x3fffffff;                        // fewest new keys any real row of this wave's tiles sees
     f32x16 acc[QT][4];
     float m_run[QT], l_run[QT];
 #pragma unroll
@@ -319,6 +320,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
         const RowInfo ri = row_info(d, r, L);
         r_vis[i] = ok ? ri.vis : 0;
         r_blk[i] = ok ? ri.blk : -2;
+        if (ok) vis_min = min(vis_min, ri.vis);
         const bf16_t *qp = a.q + (((size_t)b * d.R + r) * a.n_q + (g * a.group + hq)) * HD + 8 * lh;
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
@@ -380,8 +382,13 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
 
     const std::true_type pure_c;
     const std::false_type masked_c;
-    // leading iterations whose two units lie wholly inside the prefix
-    const int n_fast = min(max(min(a1, n_pure >> 1) - a0, 0), nA);
+    // Leading iterations whose two units every row of this wave's tiles sees in full: the prefix, and in a prefill
+    // or scoring pass also the rows of the pass that lie before the tile (all but the diagonal of a causal pass).
+    // The count differs from wave to wave; the loops below pass the same one barrier per iteration.
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) vis_min = min(vis_min, __shfl_xor(vis_min, o));
+    const int n_pure_w = __builtin_amdgcn_readfirstlane(min(n_cache_units, max(n_pure, (L + min(vis_min, d.nc)) >> 4)));
+    const int n_fast = min(max(min(a1, n_pure_w >> 1) - a0, 0), nA);
     {
         // Direct loads: wave w moves unit w/2 of the pair: for K the LDS rows 8*(w%2) .. +7 of that unit (two
         // instructions of 1 KiB: lane = (row, 16-byte slot), the slot holds piece slot ^ row%16 of the key the row
