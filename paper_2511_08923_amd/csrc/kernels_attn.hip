@@ -668,7 +668,7 @@ __global__ __launch_bounds__(64) void attn_combine_kernel(const float *__restric
 
 }  // namespace
 
-AttnPlan plan_attention(int B, int n_kv, int group, int R, int max_keys) {
+AttnPlan plan_attention(int B, int n_kv, int group, int R, int nc, int max_keys) {
     AttnPlan p;
     int TQ = (group * R + 31) / 32;           // 32-row query tiles per kv head
     p.tiles_per_chunk = TQ < 4 ? TQ : 4;      // four waves x one query tile each
@@ -680,7 +680,10 @@ AttnPlan plan_attention(int B, int n_kv, int group, int R, int max_keys) {
     // ragged).  The split count with the least estimated time wins, the smaller one on a near tie (fewer partial
     // sums for the combine kernel): 7 at batch 1 and 4096 keys (one full round), 5 at batch 4 and 8192 keys
     // (where one split left 44 % of the slots idle for the whole launch), 1 once the batch alone fills the chip
-    // several times over.
+    // several times over.  A pass with many causal rows (prefill, scoring) is another matter: its workgroups walk
+    // key ranges of very different lengths, the rounds do not end together, and no ragged last round is charged
+    // (measured on the training-layout pass of 4096 rows: two splits cost 6 ms per forward in partial sums and
+    // their combine launch, against nothing gained in the attention kernel).
     // No more than 64 splits (the combine kernel reads one per lane) and, beyond two, no more than four slot-fulls
     // of workgroups: that bound depends on the row structure alone, and the workspace is sized by it, so the
     // partial-sum area does not depend on the key bound of a particular call.
@@ -691,7 +694,7 @@ AttnPlan plan_attention(int B, int n_kv, int group, int R, int max_keys) {
     double best = 0.0;
     for (int c = 1; c <= cap; ++c) {
         const double waves = (double)base * c / 512.0;
-        const double cost = (waves <= 1.0 ? 1.0 : waves + 0.5) * ((iters + c - 1) / c + 8);
+        const double cost = (waves <= 1.0 ? 1.0 : nc >= 64 ? waves : waves + 0.5) * ((iters + c - 1) / c + 8);
         if (c == 1 || cost < 0.97 * best) {
             best = cost;
             s = c;

@@ -157,7 +157,7 @@ struct AttnPlan {
     int per;             // key-pair iterations per split, from the caller's bound on the key count (not from the
                          // sequence's current length): a key's split then depends on its position alone
 };
-AttnPlan plan_attention(int B, int n_kv, int group, int R, int max_keys);
+AttnPlan plan_attention(int B, int n_kv, int group, int R, int nc, int max_keys);
 size_t attn_partial_floats(int B, int n_kv, int group, int R, int hd, int splits);
 
 // With one split the kernel writes the result to out (row-major [rows][n_q][hd], or, out_af != 0, the A-fragment

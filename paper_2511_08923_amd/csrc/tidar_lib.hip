@@ -117,7 +117,7 @@ Layout make_layout(const tidar_config &c, int B, int R, int n_mask, int Mh, int 
     l.attn_splits = 1;
     size_t pf = 0;
     if (c.dtype == TIDAR_BF16) {
-        AttnPlan ap = plan_attention(B, c.n_kv_heads, c.n_q_heads / c.n_kv_heads, R, max_keys);
+        AttnPlan ap = plan_attention(B, c.n_kv_heads, c.n_q_heads / c.n_kv_heads, R, R - n_mask, max_keys);
         l.attn_splits = ap.splits;
         pf = attn_partial_floats(B, c.n_kv_heads, c.n_q_heads / c.n_kv_heads, R, c.head_dim, ap.splits_bound);
     }
@@ -207,7 +207,7 @@ void attention(tidar_ctx *ctx, const Layout &l, char *ws, KvView kvv, int n_page
                RowDesc d, int B, int max_keys, void *o_out, hipStream_t st) {
     const tidar_config &c = ctx->cfg;
     if (c.dtype == TIDAR_BF16) {
-        AttnPlan ap = plan_attention(B, c.n_kv_heads, c.n_q_heads / c.n_kv_heads, d.R, max_keys);
+        AttnPlan ap = plan_attention(B, c.n_kv_heads, c.n_q_heads / c.n_kv_heads, d.R, d.nc, max_keys);
         {
             Prof p(ctx, KC_ATTN, st);
             launch_attention_bf16((const bf16_t *)(ws + l.q), kvv, n_pages, (const bf16_t *)(ws + l.k_scr),
@@ -674,7 +674,7 @@ tidar_status tidar_hybrid_attention(tidar_ctx *ctx, const tidar_kv_cache *kv, in
     if (n_mt < 1) n_mt = 1;
     size_t scr = align_up((size_t)batch * c.n_kv_heads * n_mt * 16 * c.head_dim * es);
     int max_keys = max_prefix_len_hint + d.R;
-    AttnPlan ap = plan_attention(batch, c.n_kv_heads, c.n_q_heads / c.n_kv_heads, d.R, max_keys);
+    AttnPlan ap = plan_attention(batch, c.n_kv_heads, c.n_q_heads / c.n_kv_heads, d.R, d.nc, max_keys);
     size_t pf = c.dtype == TIDAR_BF16
                     ? attn_partial_floats(batch, c.n_kv_heads, c.n_q_heads / c.n_kv_heads, d.R, c.head_dim,
                                           ap.splits_bound)
