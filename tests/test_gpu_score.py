@@ -110,10 +110,10 @@ def test_score_argument_errors(T):
 SCORE_TOL = 4e-2        # a logit within 2e-2 of the oracle's and a log-sum-exp within 2e-2
 
 
-@pytest.mark.parametrize("S,bl,chunk", [(300, 16, None), (700, 8, 256), (333, 5, 100), (1100, 0, None)])
+@pytest.mark.parametrize("S,bl,chunk", [(300, 16, None), (700, 8, 256), (333, 5, 100), (1100, 0, 1024)])
 def test_small_bf16_scores_match_oracle(T, S, bl, chunk):
     """bf16 MFMA path: one pass of 600 rows; three passes of 512 rows and a ragged one; blocks of 5 that straddle
-    the 16-key tiles with a short last block; causal-only scoring in two passes of the default chunk."""
+    the 16-key tiles with a short last block; causal-only scoring in a pass of 1024 rows and one of 76."""
     sh = TI.SMALL_GQA
     w = TI.make_weights(sh, seed=3, dtype=torch.bfloat16, std=0.05)
     eng = T.Engine(sh, w, dtype=T.TIDAR_BF16, max_k=16, max_batch=1, max_seq_len=1280, prefill_chunk=chunk)

@@ -302,12 +302,14 @@ def test_bf16_fused_vocab_reduction_equals_logits_path(T, small, k):
     assert int(t1[0]) == int(t2[0]) == int(lg[0].argmax())
 
 
-def test_small_bf16_long_prompt_two_default_passes(T):
-    """A 1100-token prompt at the default prefill chunk: one pass of 1024 causal rows (33 row tiles, several GEMM row
-    passes) and a last pass of 76 causal rows plus the mask block, against the oracle's single pass."""
+@pytest.mark.parametrize("chunk", [None, 1024])
+def test_small_bf16_long_prompt_one_and_two_passes(T, chunk):
+    """A 1100-token prompt against the oracle's single pass.  At the default prefill chunk: one pass of 1100 causal
+    rows plus the mask block (35 row tiles: the many-row GEMM class in five row passes).  At 1024 rows per pass: a
+    pass of 1024 causal rows and a last one of 76 plus the mask block."""
     sh = TI.SMALL_GQA
     w = TI.make_weights(sh, seed=3, dtype=torch.bfloat16)
-    eng = T.Engine(sh, w, dtype=T.TIDAR_BF16, max_k=8, max_batch=1, max_seq_len=1280)
+    eng = T.Engine(sh, w, dtype=T.TIDAR_BF16, max_k=8, max_batch=1, max_seq_len=1280, prefill_chunk=chunk)
     model = O.OracleModel(sh, w, bf16_faithful=True)
     k, P = 8, 1100
     prompt = TI.make_prompt(sh, P, seed=91)
