@@ -158,7 +158,10 @@ def test_hybrid_attention_bf16_batch_ragged_prefixes(T):
 
 
 @pytest.mark.parametrize("nc,nb,bl,cond0,L", [(1, 0, 1, 1, 200), (1, 0, 1, 1, 0), (40, 1, 8, 40, 64),
-                                              (256, 1, 16, 256, 256), (256, 0, 16, 256, 0)])
+                                              (256, 1, 16, 256, 256), (256, 0, 16, 256, 0),
+                                              # causal passes of many tiles: the rows of the pass before a tile run
+                                              # in the loop without predicate, a different count for every wave
+                                              (600, 1, 16, 600, 77), (333, 0, 16, 333, 1000)])
 def test_hybrid_attention_bf16_ar_and_prefill_shapes(T, nc, nb, bl, cond0, L):
     print(f"attn bf16 nc={nc} nb={nb} bl={bl} L={L}", flush=True)
     for got, want in _attention_case(T, TI.SMALL_GQA, 1, [L], nc, nb, bl, cond0, seed=nc + L, dtype_id=T.TIDAR_BF16):
