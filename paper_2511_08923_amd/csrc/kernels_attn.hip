@@ -72,6 +72,7 @@ struct AttnArgs {
     RowDesc d;
     int n_q, group;
     int n_chunks, tiles_per_chunk, splits, per;
+    int n_groups;                         // batch x kv heads
     int n_pages;               // physical pages per layer (bounds of the page buffers)
     float scale_log2e;
     float *opart, *mpart, *lpart;
@@ -245,11 +246,15 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // known to be uniform: scalar registers
     const int lq = lane & 31, lh = lane >> 5;
-    int bx = blockIdx.x;
-    const int chunk = bx % a.n_chunks;
-    bx /= a.n_chunks;
-    const int g = bx % a.kv.n_kv;
-    const int b = bx / a.kv.n_kv;
+    // Workgroup i of a launch runs on XCD i % 8 (the grid's x extent is a multiple of 8, so the split index does not
+    // change that): the query chunks of one (sequence, kv head) are dealt to one XCD, whose L2 then fetches that
+    // head's K and V once instead of once per XCD that happens to run one of its chunks.
+    const int xj = blockIdx.x >> 3;
+    const int grp = (xj / a.n_chunks) * 8 + (blockIdx.x & 7);
+    if (grp >= a.n_groups) return;                   // padding of the last eight groups (whole workgroup)
+    const int chunk = xj % a.n_chunks;
+    const int g = grp % a.kv.n_kv;
+    const int b = grp / a.kv.n_kv;
     const int split = blockIdx.y;
     const RowDesc d = a.d;
     const int L = a.prefix_len[d.seq_base + b];
@@ -337,7 +342,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
     }
 
     const size_t page_elems = (size_t)a.kv.n_kv * 16 * HD;
-    const size_t scr_elems = (size_t)gridDim.x / a.n_chunks * (n_mt > 0 ? n_mt : 1) * 16 * HD;   // B * n_kv tiles
+    const size_t scr_elems = (size_t)a.n_groups * (n_mt > 0 ? n_mt : 1) * 16 * HD;   // B * n_kv tiles
     const int32_t *pt = a.kv.page_table + (size_t)(d.seq_base + b) * a.kv.pages_per_seq;
 
     // one key-pair iteration of every query tile of this wave against LDS buffer `buf`
@@ -739,7 +744,8 @@ void launch_attention_bf16(const bf16_t *q, KvView kv, int n_pages, const bf16_t
     a.opart = part;
     a.mpart = part + rows * HD;
     a.lpart = a.mpart + rows;
-    dim3 grid(B * kv.n_kv * p.n_chunks, p.splits);
+    a.n_groups = B * kv.n_kv;
+    dim3 grid((a.n_groups + 7) / 8 * 8 * p.n_chunks, p.splits);
     attn_bf16_kernel<1><<<grid, 256, 0, st>>>(a);
 }
 
