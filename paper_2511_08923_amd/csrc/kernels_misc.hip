@@ -145,7 +145,12 @@ __global__ __launch_bounds__(1024) void rmsnorm_kernel(float *__restrict__ x, co
 }
 
 // ------------------------------------------------------------------ RoPE + K/V placement
-// blockIdx.x = row, blockIdx.y = slice of the row's work.  qkv_part: tiled GEMM output, [S] x (q_dim + 2 kv_dim) columns.  Q rows -> q_out [M][q_dim];
+// blockIdx.x < rows: one row, blockIdx.y = slice of the row's work (Q rotation, K rotation and placement).
+// blockIdx.x >= rows: one 16-key V tile of one sequence (a cache page the causal rows touch, or a scratch tile of
+// the mask rows), blockIdx.y = slice of its (kv head, d) pairs.  V is kept transposed ([d][16 keys]); written row
+// by row that is one 2-byte store per value, 32 bytes apart (measured: 2.8 times the bytes at the memory side and
+// half of this kernel's time at batch 32), so the tile blocks gather by (head, d) and write whole pieces.
+// qkv_part: tiled GEMM output, [S] x (q_dim + 2 kv_dim) columns.  Q rows -> q_out [M][q_dim];
 // K/V of causal rows -> cache at position L + r; K/V of mask rows -> scratch tiles
 // k_scr [B][n_kv][n_mtiles][16][hd], v_scr [B][n_kv][n_mtiles][hd][16].
 template <typename T>
@@ -154,11 +159,78 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(const float *__restrict__ 
                                                       const int32_t *__restrict__ prefix_len, RowDesc d, int n_q,
                                                       int M_all, KvView kv, T *__restrict__ q_out,
                                                       T *__restrict__ k_scr, T *__restrict__ v_scr) {
+    const int hd = kv.hd, half = hd / 2, n_kv = kv.n_kv;
+    const int q_dim = n_q * hd, kv_dim = n_kv * hd;
+    if ((int)blockIdx.x >= M_all) {
+        // item = (kv head, d, quarter of the tile's 16 keys): four keys gathered, 8 bytes (bf16) written; the four
+        // quarters of a d are neighbouring lanes, so a wave still writes one contiguous run
+        const int n_ct = (d.nc + 15) / 16 + 1;           // cache pages the causal rows can touch
+        const int n_mtiles = (d.nm + 15) / 16;
+        const int items = n_kv * hd * 4;
+        const int per_blk = gridDim.y * blockDim.x;
+        const int parts = (items + per_blk - 1) / per_blk;
+        int vb = blockIdx.x - M_all;
+        const int part_i = vb % parts;
+        vb /= parts;
+        const int b = vb / (n_ct + n_mtiles), t = vb - b * (n_ct + n_mtiles);
+        const int idx = (part_i * gridDim.y + blockIdx.y) * blockDim.x + threadIdx.x;
+        if (idx >= items) return;
+        const int L = prefix_len[d.seq_base + b];
+        int r0, lo, hi;                                  // the tile's key s is row r0 + s; keys [lo, hi) exist
+        T *base;                                         // [n_kv][hd][16] of this tile, strided per head by hstride
+        size_t hstride;
+        if (t < n_ct) {
+            const int p = (L >> 4) + t;
+            r0 = 16 * p - L;
+            lo = max(0, -r0);
+            hi = min(16, d.nc - r0);
+            if (hi <= lo) return;
+            const int page = kv.page_table[(size_t)(d.seq_base + b) * kv.pages_per_seq + p];
+            base = (T *)kv.v_pages + v_page_offset(kv, page, 0, 0, 0);
+            hstride = (size_t)hd * 16;
+        } else {
+            const int mt = t - n_ct;
+            r0 = d.nc + 16 * mt;
+            lo = 0;
+            hi = min(16, d.nm - 16 * mt);
+            base = v_scr + (size_t)b * n_kv * n_mtiles * hd * 16 + (size_t)mt * hd * 16;
+            hstride = (size_t)n_mtiles * hd * 16;
+        }
+        const int qd = idx & 3, hdd = idx >> 2;
+        const int h = hdd / hd, dd = hdd - h * hd;
+        const int s0 = 4 * qd;
+        T *dst = base + h * hstride + (size_t)dd * 16 + s0;
+        const bool keep = t < n_ct && (s0 < lo || s0 + 4 > hi);     // slots of earlier or later tokens in this piece
+        T vals[4];
+        if (keep) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) vals[e] = dst[e];
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) vals[e] = from_f<T>(0.f);
+        }
+        const float *pp[4];
+        float v[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int s = min(max(s0 + e, lo), hi - 1);       // clamped: an existing row, value unused if outside
+            pp[e] = part + pt_index(q_dim + kv_dim + h * hd + dd, b * d.R + r0 + s, M_all);
+        }
+#pragma unroll 4
+        for (int sp = 0; sp < S; ++sp) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] += pp[e][(size_t)sp * split_stride];
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (s0 + e >= lo && s0 + e < hi) vals[e] = from_f<T>(v[e]);
+        typedef T vec4 __attribute__((ext_vector_type(4)));
+        *(vec4 *)dst = (vec4){vals[0], vals[1], vals[2], vals[3]};
+        return;
+    }
     const int row = blockIdx.x;
     const int b = row / d.R;
     const int r = row - b * d.R;
-    const int hd = kv.hd, half = hd / 2, n_kv = kv.n_kv;
-    const int q_dim = n_q * hd, kv_dim = n_kv * hd;
     const int per_head = half / 4;                   // groups of four rotation pairs
     const float *cs = rope_cs + (size_t)row * half * 2;
     auto val4 = [&](int col) {
@@ -207,30 +279,20 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(const float *__restrict__ 
         slot = m & 15;
     }
     T *kp = (T *)kv.k_pages;
-    T *vp = (T *)kv.v_pages;
     for (int idx = (blockIdx.y - q_blocks) * blockDim.x + threadIdx.x; idx < n_kv * per_head;
          idx += (gridDim.y - q_blocks) * blockDim.x) {
         int h = idx / per_head, i = 4 * (idx - h * per_head);
         float4 lo, hi;
         rotate(val4(q_dim + h * hd + i), val4(q_dim + h * hd + i + half), i, lo, hi);
-        float4 v0 = val4(q_dim + kv_dim + h * hd + i), v1 = val4(q_dim + kv_dim + h * hd + i + half);
-        T *kdst, *vdst;            // K: [slot][hd] contiguous in d;  V: [d][16] strided by 16 in d
+        T *kdst;                   // K: [slot][hd] contiguous in d (V goes by tiles, above)
         if (causal) {
             kdst = kp + k_page_offset(kv, page, h, slot, 0);
-            vdst = vp + v_page_offset(kv, page, h, slot, 0);
         } else {
             size_t tile = ((size_t)b * n_kv + h) * n_mtiles + mt;
             kdst = k_scr + (tile * 16 + slot) * hd;
-            vdst = v_scr + tile * hd * 16 + slot;
         }
         store4<T>(kdst + i, lo.x, lo.y, lo.z, lo.w);
         store4<T>(kdst + i + half, hi.x, hi.y, hi.z, hi.w);
-        const float vv0[4] = {v0.x, v0.y, v0.z, v0.w}, vv1[4] = {v1.x, v1.y, v1.z, v1.w};
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            vdst[(size_t)(i + e) * 16] = from_f<T>(vv0[e]);
-            vdst[(size_t)(i + half + e) * 16] = from_f<T>(vv1[e]);
-        }
     }
 }
 
@@ -744,7 +806,10 @@ void launch_rope_kv(int dtype, const float *qkv_part, int S, const float *rope_c
     int rows = B * d.R;
     size_t stride = pt_split_stride(rows, (n_q + 2 * kv.n_kv) * kv.hd);
     const int per_head = kv.hd / 8;                  // items (four rotation pairs) per head
-    dim3 grid(rows, (n_q * per_head + 255) / 256 + (kv.n_kv * per_head + 255) / 256);
+    const int gy = (n_q * per_head + 255) / 256 + (kv.n_kv * per_head + 255) / 256;
+    const int v_parts = (kv.n_kv * kv.hd * 4 + gy * 256 - 1) / (gy * 256);      // see the kernel's V-tile branch
+    const int v_tiles = B * ((d.nc + 15) / 16 + 1 + (d.nm + 15) / 16);
+    dim3 grid(rows + v_tiles * v_parts, gy);
     if (dtype == TIDAR_BF16)
         rope_kv_kernel<bf16_t><<<grid, 256, 0, st>>>(qkv_part, S, stride, rope_cs, prefix_len, d, n_q, rows, kv,
                                                       (bf16_t *)q_out, (bf16_t *)k_scr, (bf16_t *)v_scr);
