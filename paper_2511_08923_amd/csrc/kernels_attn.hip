@@ -73,6 +73,7 @@ struct AttnArgs {
     int n_q, group;
     int n_chunks, tiles_per_chunk, splits, per;
     int n_groups;                         // batch x kv heads
+    int xcd_q;                            // 0: plain order; q >= 1: a group's chunks go to q XCDs (see the kernel)
     int n_pages;               // physical pages per layer (bounds of the page buffers)
     float scale_log2e;
     float *opart, *mpart, *lpart;
@@ -246,13 +247,24 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // known to be uniform: scalar registers
     const int lq = lane & 31, lh = lane >> 5;
-    // Workgroup i of a launch runs on XCD i % 8 (the grid's x extent is a multiple of 8, so the split index does not
-    // change that): the query chunks of one (sequence, kv head) are dealt to one XCD, whose L2 then fetches that
-    // head's K and V once instead of once per XCD that happens to run one of its chunks.
-    const int xj = blockIdx.x >> 3;
-    const int grp = (xj / a.n_chunks) * 8 + (blockIdx.x & 7);
-    if (grp >= a.n_groups) return;                   // padding of the last eight groups (whole workgroup)
-    const int chunk = xj % a.n_chunks;
+    // Workgroup i of a launch runs on XCD i % 8 (the grid's x extent is then a multiple of 8, so the split index
+    // does not change that).  Where the (sequence, kv head) groups divide evenly over the XCDs, or the XCDs over
+    // the groups, the query chunks of one group are dealt to one XCD (or to 8 / groups of them), whose L2 then
+    // fetches that head's K and V once instead of once per XCD that happens to run one of its chunks.
+    int grp, chunk;
+    if (a.xcd_q == 0) {
+        chunk = blockIdx.x % a.n_chunks;
+        grp = blockIdx.x / a.n_chunks;
+    } else if (a.n_groups >= 8) {
+        const int xj = blockIdx.x >> 3;
+        grp = (xj / a.n_chunks) * 8 + (blockIdx.x & 7);
+        chunk = xj % a.n_chunks;
+    } else {
+        const int xcd = blockIdx.x & 7;
+        grp = xcd / a.xcd_q;
+        chunk = (blockIdx.x >> 3) * a.xcd_q + xcd % a.xcd_q;
+        if (chunk >= a.n_chunks) return;             // padding of the last round (whole workgroup)
+    }
     const int g = grp % a.kv.n_kv;
     const int b = grp / a.kv.n_kv;
     const int split = blockIdx.y;
@@ -745,7 +757,9 @@ void launch_attention_bf16(const bf16_t *q, KvView kv, int n_pages, const bf16_t
     a.mpart = part + rows * HD;
     a.lpart = a.mpart + rows;
     a.n_groups = B * kv.n_kv;
-    dim3 grid((a.n_groups + 7) / 8 * 8 * p.n_chunks, p.splits);
+    a.xcd_q = a.n_groups % 8 == 0 ? 1 : (a.n_groups < 8 && 8 % a.n_groups == 0) ? 8 / a.n_groups : 0;
+    dim3 grid(a.n_groups * p.n_chunks, p.splits);
+    if (a.xcd_q > 1) grid.x = 8 * ((p.n_chunks + a.xcd_q - 1) / a.xcd_q);
     attn_bf16_kernel<1><<<grid, 256, 0, st>>>(a);
 }
 
