@@ -58,7 +58,9 @@ Readings taken where the paper is silent (figures are not available):
 
 Parity status: every function below is pinned by tests/test_oracle_*.py
 (worked-example mask, closed-form counts, brute-force loops, an independent
-library transformer, AR-equivalence, cache equality).  The *values* of the
+library transformer, AR-equivalence, cache equality; the beta-mix of
+Section 4.3.3 against a verifier assembled from separate prefill-style
+forwards, one per draft count, which never touches the step's row helpers).  The *values* of the
 diffusion-row logits have no pin beyond those structural ones: no trained
 weights exist here, so for them the status is "parity unpinned".
 """

@@ -172,3 +172,92 @@ def test_bf16_faithful_mode_stays_close_to_exact(prompt):
     _, l2 = faithful.prefill(s2, prompt, 4)
     err = float((l1 - l2).abs().max())
     assert 0.0 < err < 2e-2
+
+
+def _mixed_verification_by_separate_forwards(model, text, drafts, beta):
+    """What Section 4.3.3 asks of a step, built without the step: for every i, ONE prefill-style forward over
+    [text + c_1..c_i ; k masks] gives the causal logits of c_i (last text row) and the logits of the first mask
+    slot, both predicting the token after c_i; the verifier's token is the argmax of their beta-mix.  Returns
+    (acceptance length, the verifier's token at the first unverified position, all k verifier tokens)."""
+    k = len(drafts)
+    y = []
+    for i in range(1, k + 1):
+        fresh = model.new_state(len(text) + 2 * k + 2)
+        _, lg = model.prefill(fresh, list(text) + list(drafts[:i]), k)      # rows: last text row, mask slots 1..k
+        y.append(int(torch.argmax(beta * lg[0] + (1.0 - beta) * lg[1])))
+    a = 1
+    while a < k and drafts[a] == y[a - 1]:
+        a += 1
+    return a, y[a - 1], y
+
+
+@pytest.fixture(scope="module")
+def sharp_model():
+    """Weights ten times wider than the default recipe: with N(0, 0.02) the mask rows of this untrained tiny model all
+    choose the same token, so that no pairing of rows could be told from another; at 0.2 every slot of every block
+    has its own prediction."""
+    return O.OracleModel(SHAPE, TI.make_weights(SHAPE, seed=1, std=0.2))
+
+
+@pytest.mark.parametrize("beta", [0.0, 0.3, 1.0])
+def test_beta_mix_pairs_each_causal_row_with_the_first_slot_of_its_own_block(sharp_model, prompt, beta, monkeypatch):
+    """Pin of Mode.beta that does not reuse the step's own mix line or row helpers: the step's acceptance length
+    and first next-draft must equal those of a verifier assembled from separate prefill-style forwards (one per
+    draft count), for drafts built to be accepted up to a chosen length.  beta = 0 is verification by the
+    diffusion logits alone, beta = 1 the default.  A planted wrong pairing (another slot, another block) in the
+    oracle must fail the same comparison."""
+    model = sharp_model
+    k = 4
+    st = model.new_state(160)
+    drafts, _ = model.prefill(st, prompt, k)
+    text = list(prompt)
+    mode = O.Mode(beta=beta)
+    differs_from_default = False
+    for step in range(4):
+        # drafts the mixed verifier accepts up to length `want_a`: take its own tokens, then a wrong one
+        want_a = 1 + step % k
+        c = [drafts[0]]
+        for i in range(1, k):
+            _, _, y = _mixed_verification_by_separate_forwards(model, text, c + [0] * (k - len(c)), beta)
+            c.append(y[i - 1] if i < want_a else (y[i - 1] + 1) % (SHAPE.vocab - 1))
+        a_ref, nxt0_ref, y_ref = _mixed_verification_by_separate_forwards(model, text, c, beta)
+        assert a_ref == want_a
+        _, _, y_default = _mixed_verification_by_separate_forwards(model, text, c, 1.0)
+        differs_from_default |= y_ref != y_default
+        probe = O.State([t.clone() for t in st.k], [t.clone() for t in st.v], st.L, st.seq_id)
+        a, accepted, nxt, _ = model.tidar_step(st, c, mode)
+        assert (a, nxt[0]) == (a_ref, nxt0_ref), (step, a, a_ref)
+        assert accepted == c[:a]
+        if beta != 1.0 and step == 3:
+            # the same comparison must catch a wrong pairing planted in the oracle
+            # (planted in the mix line alone: mask and positions of the planted runs are the real ones, computed
+            # before the helper is replaced; a helper replaced everywhere would only relabel the blocks)
+            real = O.row_of_blk
+            real_mask, real_pos = O.decode_mask(k, probe.L), O.decode_positions(k, probe.L)
+            monkeypatch.setattr(O, "decode_mask", lambda kk, LL: real_mask)
+            monkeypatch.setattr(O, "decode_positions", lambda kk, LL: real_pos)
+            for wrong in (lambda kk, j, s: real(kk, j, s + 1 if s == 1 else s),            # second slot
+                          lambda kk, j, s: real(kk, j % kk + 1 if s == 1 else j, s),        # next block
+                          lambda kk, j, s: real(kk, (j - 2) % kk + 1 if s == 1 else j, s)):  # previous block
+                p2 = O.State([t.clone() for t in probe.k], [t.clone() for t in probe.v], probe.L, probe.seq_id)
+                monkeypatch.setattr(O, "row_of_blk", wrong)
+                a_bad, _, nxt_bad, _ = model.tidar_step(p2, c, mode)
+                monkeypatch.setattr(O, "row_of_blk", real)
+                assert (a_bad, nxt_bad[0]) != (a_ref, nxt0_ref)
+            monkeypatch.undo()
+        text += accepted
+        drafts = nxt
+    if beta != 1.0:
+        assert differs_from_default          # the mix really changed at least one verifier token
+
+
+def test_beta_one_equals_the_default_step(model, prompt):
+    k = 4
+    s1, s2 = model.new_state(128), model.new_state(128)
+    d1, _ = model.prefill(s1, prompt, k)
+    d2, _ = model.prefill(s2, prompt, k)
+    for _ in range(3):
+        r1 = model.tidar_step(s1, d1)
+        r2 = model.tidar_step(s2, d2, O.Mode(beta=1.0))
+        assert r1[:3] == r2[:3] and torch.equal(r1[3], r2[3])
+        d1, d2 = r1[2], r2[2]
