@@ -17,6 +17,16 @@
  *     synchronising.
  *   - Argument and capacity errors are found on the host before anything is
  *     enqueued; a failing call has no effect on device memory.
+ *   - What only the device knows is checked by the kernels, after the call has
+ *     returned: a prefix_len[b] that is negative or, with the rows of the call,
+ *     runs past pages_per_seq * 16 (the host saw only the caller's bound); a
+ *     page-table entry outside [0, n_pages) under a position the call writes; a
+ *     token id outside [0, vocab); a logits row without a single number (all
+ *     NaN) where a token has to be chosen.  Such a sequence never makes the
+ *     kernels touch memory outside the caller's buffers (lengths are clamped,
+ *     bad ids replaced, unsafe K/V stores skipped) and is reported through its
+ *     outputs, each entry point says how; the other sequences of the batch are
+ *     not affected.
  *   - dtype 1 (bf16): activations, Q/K/V and weights are bf16, the residual
  *     stream and all accumulation are fp32.  dtype 0 (fp32): everything fp32.
  *   - Indices in comments are 0-based.
@@ -155,6 +165,7 @@ tidar_status tidar_workspace_bytes(const tidar_ctx *ctx, int32_t batch, int32_t 
  *   first_drafts dev int32 [batch][k] out: slot 0 = token chosen from the causal
  *               logits of the last prompt row (final), slots 1..k-1 = argmax of mask slots 1..k-1
  *   logits_out  optional dev fp32 [batch][1+k][vocab]: last prompt row, then the k mask rows
+ * A sequence that fails a device-side check (token id, page id) gets prefix_len[b] = -1 and first_drafts[b][*] = -1.
  */
 tidar_status tidar_prefill(tidar_ctx *ctx, const tidar_weights *w, const tidar_kv_cache *kv, int32_t batch,
                            const int32_t *prompt, int32_t prompt_stride, const int32_t *prompt_len, int32_t k,
@@ -179,6 +190,8 @@ tidar_status tidar_prefill(tidar_ctx *ctx, const tidar_weights *w, const tidar_k
  *               at every step; a bound far above the real length leaves the later splits empty (slower, still
  *               correct).
  * `drafts` may alias `next_drafts`.
+ * A sequence that fails a device-side check (see the conventions above) gets accepted_len[b] = 0,
+ * accepted_tokens[b][*] = next_drafts[b][*] = -1 and keeps its prefix_len[b].
  * The library keeps no per-sequence state: a call covers sequences 0..batch-1 of the arrays it is given, so a
  * run of sequences inside a larger batch is addressed by offsetting prefix_len, drafts, the outputs and
  * kv->page_table (by pages_per_seq entries per sequence).  That is how sequences with different k are stepped
@@ -195,6 +208,7 @@ tidar_status tidar_step(tidar_ctx *ctx, const tidar_weights *w, const tidar_kv_c
  * one token slot per forward): token_in[b] is appended at prefix_len[b], its
  * K/V committed, prefix_len += 1, token_out[b] = token chosen from its logits.
  *   logits_out optional dev fp32 [batch][vocab]
+ * A sequence that fails a device-side check gets token_out[b] = -1 and keeps its prefix_len[b].
  */
 tidar_status tidar_ar_step(tidar_ctx *ctx, const tidar_weights *w, const tidar_kv_cache *kv, int32_t batch,
                            int32_t *prefix_len, const int32_t *token_in, const tidar_mode *mode,

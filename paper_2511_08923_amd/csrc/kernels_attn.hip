@@ -27,8 +27,6 @@
 // Keys come in units of 16: cache pages 0 .. ceil((L+nc)/16)-1, then the mask rows' scratch tiles.  Pages that
 // lie wholly below L need no mask at all (every row sees the whole prefix); everything else goes through the
 // (row, key) predicate and a per-(query tile, key pair) skip when nothing is visible.
-#include <stdlib.h>
-
 #include <type_traits>
 
 #include "tidar_internal.h"
@@ -74,7 +72,6 @@ struct AttnArgs {
     int n_chunks, tiles_per_chunk, splits, per;
     int n_groups;                         // batch x kv heads
     int xcd_q;                            // 0: plain order; q >= 1: a group's chunks go to q XCDs (see the kernel)
-    int n_pages;               // physical pages per layer (bounds of the page buffers)
     float scale_log2e;
     float *opart, *mpart, *lpart;
     bf16_t *out;               // single split only: [rows][n_q][HD], or the A-fragment layout (out_af)
@@ -269,7 +266,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
     const int b = grp / a.kv.n_kv;
     const int split = blockIdx.y;
     const RowDesc d = a.d;
-    const int L = a.prefix_len[d.seq_base + b];
+    const int L = clamp_prefix(a.kv, a.prefix_len[d.seq_base + b], d.nc);   // never walks past the page table
     const int n_mask = d.nm;
     const int n_cache_units = (L + d.nc + 15) >> 4;
     const int n_pure = L >> 4;
@@ -436,8 +433,8 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
         for (int i = 0; i < QT; ++i)
 #pragma unroll
             for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+v"(qf[i][ks]));
-        const int4v dk = raw_desc(a.kv.k_pages, (size_t)a.n_pages * page_elems * 2);
-        const int4v dv = raw_desc(a.kv.v_pages, (size_t)a.n_pages * page_elems * 2);
+        const int4v dk = raw_desc(a.kv.k_pages, (size_t)a.kv.n_pages * page_elems * 2);
+        const int4v dv = raw_desc(a.kv.v_pages, (size_t)a.kv.n_pages * page_elems * 2);
         const int4v dks = raw_desc(a.k_scr, scr_elems * 2), dvs = raw_desc(a.v_scr, scr_elems * 2);
         typedef __attribute__((address_space(3))) unsigned char lds_byte;
         const unsigned k_lds0 = (unsigned)(size_t)(lds_byte *)reinterpret_cast<unsigned char *>(&k_lds[0][0]);
@@ -718,10 +715,6 @@ AttnPlan plan_attention(int B, int n_kv, int group, int R, int nc, int max_keys)
         }
     }
     p.splits = s < 1 ? 1 : s;
-    if (const char *e = getenv("TIDAR_ATTN_SPLITS")) {     // tuning override for sweeps (unset in normal use)
-        int v = atoi(e);
-        if (v >= 1 && v <= 64) p.splits = v < cap ? v : (cap < 1 ? 1 : cap);
-    }
     p.per = (iters + 1 + p.splits - 1) / p.splits;   // +1: the kernel counts cache and scratch units separately
     return p;
 }
@@ -730,7 +723,7 @@ size_t attn_partial_floats(int B, int n_kv, int group, int R, int hd, int splits
     return (size_t)B * n_kv * splits * group * R * (hd + 2);
 }
 
-void launch_attention_bf16(const bf16_t *q, KvView kv, int n_pages, const bf16_t *k_scr, const bf16_t *v_scr,
+void launch_attention_bf16(const bf16_t *q, KvView kv, const bf16_t *k_scr, const bf16_t *v_scr,
                            const int32_t *prefix_len, RowDesc d, int B, int n_q, const AttnPlan &p, float *part,
                            bf16_t *out, int out_af, hipStream_t st) {
     AttnArgs a;
@@ -749,7 +742,6 @@ void launch_attention_bf16(const bf16_t *q, KvView kv, int n_pages, const bf16_t
     a.tiles_per_chunk = p.tiles_per_chunk;
     a.splits = p.splits;
     a.per = p.per;
-    a.n_pages = n_pages;
     a.scale_log2e = 1.4426950408889634f / sqrtf((float)kv.hd);
     size_t F = (size_t)a.group * d.R;
     size_t rows = (size_t)B * kv.n_kv * p.splits * F;

@@ -30,8 +30,6 @@
 // 16x16x32: A lane l = row l%16, k slots 8*(l/16)..+7; B lane l = column l%16, same k slots; D lane l register i
 // = row 4*(l/16)+i, column l%16.   32x32x16: A lane l = row l%32, k slots 8*(l/32)..+7; B lane l = column l%32;
 // D lane l register i = row 8*(i/4) + 4*(l/32) + i%4, column l%32.
-#include <stdlib.h>
-
 #include "tidar_internal.h"
 
 namespace {
@@ -610,11 +608,6 @@ GemmPlan plan_gemm_bf16(int M, int N, int K, bool force_single_split) {
         }
         p.m_chunks = (t + ctl - 1) / ctl;
     }
-    static const int env_splits = [] {                   // tuning override for sweeps (unset in normal use)
-        const char *e = getenv("TIDAR_GEMM_SPLITS");
-        return e ? atoi(e) : 0;
-    }();
-    if (env_splits >= 1 && !force_single_split) splits = fit(env_splits);
     p.splits = splits;
     return p;
 }

@@ -1,8 +1,6 @@
 // Small kernels of the decode step: weight packing, row assembly + embedding gather, RMSNorm with fused
 // residual/split-K reduction, RoPE + K/V placement, SwiGLU, vocabulary argmax / Gumbel-max, verify/accept.
 // Also the fp32-mode GEMM and attention (plain ALU kernels used by the fp32 configuration).
-#include <stdlib.h>
-
 #include "tidar_internal.h"
 
 namespace {
@@ -70,14 +68,16 @@ __global__ void pack_f32_kernel(const float *__restrict__ src, int rows, int K, 
 template <typename T>
 __global__ void embed_rows_kernel(const T *__restrict__ embed, const int32_t *__restrict__ tokens, int tok_stride,
                                   const int32_t *__restrict__ prefix_len, RowDesc d, int d_model, int mask_id,
-                                  int hd, float rope_base, float *__restrict__ x, int32_t *__restrict__ pos_out,
-                                  float *__restrict__ rope_cs) {
+                                  int vocab, KvView kv, int hd, float rope_base, float *__restrict__ x,
+                                  int32_t *__restrict__ pos_out, float *__restrict__ rope_cs) {
     int row = blockIdx.x;                 // b * R + r
     int b = row / d.R;
     int r = row - b * d.R;
-    int L = prefix_len[d.seq_base + b];
+    int L = clamp_prefix(kv, prefix_len[d.seq_base + b], d.nc);
     RowInfo ri = row_info(d, r, L);
     int tok = (r < d.nc) ? tokens[(size_t)b * tok_stride + r] : mask_id;
+    if ((unsigned)tok >= (unsigned)vocab) tok = mask_id;      // an id outside the table is never dereferenced (the
+                                                              // kernel that finishes the call reports it)
     if (threadIdx.x == 0) pos_out[row] = ri.pos;
     const T *e = embed + (size_t)tok * d_model;
     float *xo = x + (size_t)row * d_model;
@@ -175,17 +175,20 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(const float *__restrict__ 
         const int b = vb / (n_ct + n_mtiles), t = vb - b * (n_ct + n_mtiles);
         const int idx = (part_i * gridDim.y + blockIdx.y) * blockDim.x + threadIdx.x;
         if (idx >= items) return;
-        const int L = prefix_len[d.seq_base + b];
+        const int L_raw = prefix_len[d.seq_base + b];
+        const int L = clamp_prefix(kv, L_raw, d.nc);
         int r0, lo, hi;                                  // the tile's key s is row r0 + s; keys [lo, hi) exist
         T *base;                                         // [n_kv][hd][16] of this tile, strided per head by hstride
         size_t hstride;
         if (t < n_ct) {
+            if (!seq_fits(kv, L_raw, d.nc)) return;      // a sequence that does not fit stores nothing in the cache
             const int p = (L >> 4) + t;
             r0 = 16 * p - L;
             lo = max(0, -r0);
             hi = min(16, d.nc - r0);
             if (hi <= lo) return;
             const int page = kv.page_table[(size_t)(d.seq_base + b) * kv.pages_per_seq + p];
+            if (!page_ok(kv, page)) return;
             base = (T *)kv.v_pages + v_page_offset(kv, page, 0, 0, 0);
             hstride = (size_t)hd * 16;
         } else {
@@ -266,13 +269,15 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(const float *__restrict__ 
     }
     // destination of this row's K/V
     const bool causal = r < d.nc;
-    const int L = prefix_len[d.seq_base + b];
+    const int L_raw = prefix_len[d.seq_base + b];
+    const int L = clamp_prefix(kv, L_raw, d.nc);
     int page = 0, slot = 0, mt = 0;
     const int n_mtiles = (d.nm + 15) / 16;
     if (causal) {
         int p = L + r;
         page = kv.page_table[(size_t)(d.seq_base + b) * kv.pages_per_seq + (p >> 4)];
         slot = p & 15;
+        if (!seq_fits(kv, L_raw, d.nc) || !page_ok(kv, page)) return;     // nothing of this row reaches the cache
     } else {
         int m = r - d.nc;
         mt = m >> 4;
@@ -306,13 +311,15 @@ __global__ void place_kv_kernel(const T *__restrict__ k_new, const T *__restrict
     int r = row - b * d.R;
     int hd = kv.hd, n_kv = kv.n_kv;
     bool causal = r < d.nc;
-    int L = prefix_len[d.seq_base + b];
+    const int L_raw = prefix_len[d.seq_base + b];
+    int L = clamp_prefix(kv, L_raw, d.nc);
     int page = 0, slot = 0, mt = 0;
     int n_mtiles = (d.nm + 15) / 16;
     if (causal) {
         int p = L + r;
         page = kv.page_table[(size_t)(d.seq_base + b) * kv.pages_per_seq + (p >> 4)];
         slot = p & 15;
+        if (!seq_fits(kv, L_raw, d.nc) || !page_ok(kv, page)) return;
     } else {
         int m = r - d.nc;
         mt = m >> 4;
@@ -416,7 +423,7 @@ __global__ void argmax_rows_kernel(const float *__restrict__ logits, int Rh, int
     if (threadIdx.x == 0) {
         for (int w = 1; w < (int)(blockDim.x >> 6); ++w)
             if (sb[w] > best || (sb[w] == best && si[w] < best_i)) { best = sb[w]; best_i = si[w]; }
-        y[row] = best_i;
+        y[row] = best_i == 0x7fffffff ? -1 : best_i;     // a row without a single number (all NaN) has no token
     }
 }
 
@@ -439,6 +446,10 @@ __global__ __launch_bounds__(1024) void score_rows_kernel(const float *__restric
         return;
     }
     const int label = text[li];
+    if ((unsigned)label >= (unsigned)vocab) {     // uniform over the block: an id outside the vocabulary scores NaN
+        if (threadIdx.x == 0) *dst = __builtin_nanf("");
+        return;
+    }
     __shared__ float red[16];
     __shared__ float bc;
     const int nw = blockDim.x >> 6;
@@ -498,40 +509,84 @@ __global__ __launch_bounds__(256) void score_loss_kernel(const float *__restrict
 }
 
 // ------------------------------------------------------------------ verify / accept / commit / next-draft select
-// y: [B][k(k+1)] chosen token per row (rows: c_0..c_{k-1}, blk_0[0..k), ...).  One thread per sequence.
-__global__ void verify_step_kernel(const int32_t *__restrict__ y, const int32_t *__restrict__ drafts, int k, int B,
-                                   int32_t *__restrict__ prefix_len, int32_t *__restrict__ accepted_len,
-                                   int32_t *__restrict__ accepted_tokens, int32_t *__restrict__ next_drafts) {
-    int b = blockIdx.x * blockDim.x + threadIdx.x;
-    if (b >= B) return;
-    int R = k * (k + 1);
+// y: [B][k(k+1)] chosen token per row (rows: c_0..c_{k-1}, blk_0[0..k), ...).  One wavefront per sequence: lane i
+// holds draft i, the token its causal row chose and the verdict "draft i is what row i-1 chose"; the acceptance
+// length is the position of the first lane that says no.  The same wavefront is the call's device-side checker:
+// a sequence that did not fit the page table, that wrote through a page id outside the pool, that was fed a token
+// id outside the vocabulary or whose needed rows chose no token (all NaN) is reported with accepted_len 0, its
+// tokens -1 and its prefix length untouched (the forward stored nothing of it where the store was unsafe).
+__global__ __launch_bounds__(64) void verify_step_kernel(const int32_t *__restrict__ y,
+                                                         const int32_t *__restrict__ drafts, int k, int vocab,
+                                                         KvView kv, int seq_base, int32_t *__restrict__ prefix_len,
+                                                         int32_t *__restrict__ accepted_len,
+                                                         int32_t *__restrict__ accepted_tokens,
+                                                         int32_t *__restrict__ next_drafts) {
+    const int b = blockIdx.x, lane = threadIdx.x;
+    const int R = k * (k + 1);
     const int32_t *yb = y + (size_t)b * R;
-    int32_t c[TIDAR_MAX_K];
-    for (int i = 0; i < k; ++i) c[i] = drafts[(size_t)b * k + i];
-    int a = 1;                                              // c_0 is final already
-    while (a < k && c[a] == yb[a - 1]) ++a;                 // causal row a-1 judges draft a
-    accepted_len[b] = a;
-    for (int i = 0; i < k; ++i) accepted_tokens[(size_t)b * k + i] = (i < a) ? c[i] : -1;
-    next_drafts[(size_t)b * k] = yb[a - 1];                 // token at the first unverified position
-    for (int s = 1; s < k; ++s) next_drafts[(size_t)b * k + s] = yb[k + (a - 1) * k + s];
-    prefix_len[b] += a;                                     // commit: rejected drafts' K/V fall behind the frontier
+    const int L = prefix_len[b];
+    const bool fits = seq_fits(kv, L, k);
+    const bool mine = lane < k;
+    const int c = mine ? drafts[(size_t)b * k + lane] : 0;
+    const int y_prev = (mine && lane > 0) ? yb[lane - 1] : 0;            // causal row i-1 judges draft i
+    bool bad = mine && (unsigned)c >= (unsigned)vocab;
+    if (mine && fits) {
+        const int page = kv.page_table[(size_t)(seq_base + b) * kv.pages_per_seq + ((L + lane) >> 4)];
+        bad = bad || !page_ok(kv, page);
+    }
+    const unsigned long long no = __ballot(mine && lane > 0 && c != y_prev) | (1ull << k);
+    const int a = __ffsll((long long)no) - 1;                            // first rejected draft = tokens accepted, 1..k
+    const int nxt = !mine ? 0 : lane == 0 ? yb[a - 1] : yb[k + (a - 1) * k + lane];
+    bad = bad || (mine && nxt < 0);
+    const bool err = !fits || __ballot(bad) != 0ull;
+    if (mine) {
+        accepted_tokens[(size_t)b * k + lane] = (!err && lane < a) ? c : -1;
+        next_drafts[(size_t)b * k + lane] = err ? -1 : nxt;
+    }
+    if (lane == 0) {
+        accepted_len[b] = err ? 0 : a;
+        if (!err) prefix_len[b] = L + a;           // commit: rejected drafts' K/V fall behind the frontier
+    }
 }
 
-__global__ void finish_ar_kernel(const int32_t *__restrict__ y, int B, int32_t *__restrict__ prefix_len,
-                                 int32_t *__restrict__ token_out) {
+__global__ __launch_bounds__(64) void finish_ar_kernel(const int32_t *__restrict__ y,
+                                                       const int32_t *__restrict__ token_in, int B, int vocab,
+                                                       KvView kv, int32_t *__restrict__ prefix_len,
+                                                       int32_t *__restrict__ token_out) {
     int b = blockIdx.x * blockDim.x + threadIdx.x;
     if (b >= B) return;
-    token_out[b] = y[b];
-    prefix_len[b] += 1;
+    const int L = prefix_len[b];
+    bool err = !seq_fits(kv, L, 1) || (unsigned)token_in[b] >= (unsigned)vocab || y[b] < 0;
+    if (!err) err = !page_ok(kv, kv.page_table[(size_t)b * kv.pages_per_seq + (L >> 4)]);
+    token_out[b] = err ? -1 : y[b];
+    if (!err) prefix_len[b] = L + 1;
 }
 
-__global__ void finish_prefill_kernel(const int32_t *__restrict__ y, int k, int seq, int add_len, int last,
-                                      int32_t *__restrict__ prefix_len, int32_t *__restrict__ first_drafts) {
-    if (threadIdx.x == 0) prefix_len[seq] += add_len;
-    if (last && threadIdx.x < k) {
-        // y rows: last prompt row, then mask slots 0..k-1; slot 0 of the block is superseded by the causal token
-        first_drafts[(size_t)seq * k + threadIdx.x] = (threadIdx.x == 0) ? y[0] : y[1 + threadIdx.x];
+// One wavefront per prefill pass over prompt positions [L, L + add_len) of sequence `seq`.  A pass that was fed a
+// token id outside the vocabulary or met a page id outside the pool marks the sequence: prefix_len = -1, which
+// keeps every later pass from storing anything for it, and first_drafts = -1.
+__global__ __launch_bounds__(64) void finish_prefill_kernel(const int32_t *__restrict__ y,
+                                                            const int32_t *__restrict__ tokens, int k, int seq,
+                                                            int add_len, int last, int vocab, KvView kv,
+                                                            int32_t *__restrict__ prefix_len,
+                                                            int32_t *__restrict__ first_drafts) {
+    const int lane = threadIdx.x;
+    const int L = prefix_len[seq];
+    bool bad = !seq_fits(kv, L, add_len);
+    if (!bad) {
+        for (int i = lane; i < add_len; i += 64) bad = bad || (unsigned)tokens[i] >= (unsigned)vocab;
+        for (int p = (L >> 4) + lane; p <= ((L + add_len - 1) >> 4); p += 64)
+            bad = bad || !page_ok(kv, kv.page_table[(size_t)seq * kv.pages_per_seq + p]);
     }
+    // y rows: last prompt row, then mask slots 0..k-1; slot 0 of the block is superseded by the causal token
+    int tok = 0;
+    if (last && lane < k) {
+        tok = (lane == 0) ? y[0] : y[1 + lane];
+        bad = bad || tok < 0;
+    }
+    const bool err = __ballot(bad) != 0ull;
+    if (lane == 0) prefix_len[seq] = err ? -1 : L + add_len;
+    if ((last || err) && lane < k) first_drafts[(size_t)seq * k + lane] = err ? -1 : tok;
 }
 
 // plain row-major [M][K] -> A-fragment layout (8 elements per thread)
@@ -603,7 +658,7 @@ __global__ __launch_bounds__(1024) void argmax_groups_kernel(const float *__rest
         }
         __syncthreads();
     }
-    if (sl == 0 && row < M) y[row] = bi == 0x7fffffff ? 0 : bi;
+    if (sl == 0 && row < M) y[row] = bi == 0x7fffffff ? -1 : bi;      // same rule as argmax_rows_kernel
 }
 
 __global__ void set_i32_kernel(int32_t *p, int n, int32_t v) {
@@ -658,7 +713,7 @@ __global__ __launch_bounds__(64) void attention_f32_kernel(const float *__restri
     int b = row / d.R, r = row - b * d.R;
     int hd = kv.hd, n_kv = kv.n_kv;
     int g = head / (n_q / n_kv);
-    int L = prefix_len[d.seq_base + b];
+    int L = clamp_prefix(kv, prefix_len[d.seq_base + b], d.nc);
     RowInfo ri = row_info(d, r, L);
     int n_cache = L + d.nc, n_mask = d.nm, n_mtiles = (n_mask + 15) / 16;
     int T = n_cache + n_mask;
@@ -679,7 +734,8 @@ __global__ __launch_bounds__(64) void attention_f32_kernel(const float *__restri
         const float *krow = nullptr;
         if (t < n_cache) {
             vis = (t < L) || (t - L < ri.vis);
-            krow = kp + k_page_offset(kv, pt[t >> 4], g, t & 15, 0);
+            const int page = pt[t >> 4];
+            krow = kp + k_page_offset(kv, page_ok(kv, page) ? page : 0, g, t & 15, 0);
         } else if (t < T) {
             int m = t - n_cache;
             vis = (ri.blk >= 0) && (m / d.bl == ri.blk);
@@ -710,7 +766,8 @@ __global__ __launch_bounds__(64) void attention_f32_kernel(const float *__restri
             const float *vbase;
             size_t stride_d;
             if (tj < n_cache) {
-                vbase = vp + v_page_offset(kv, pt[tj >> 4], g, tj & 15, 0);
+                const int page = pt[tj >> 4];
+                vbase = vp + v_page_offset(kv, page_ok(kv, page) ? page : 0, g, tj & 15, 0);
                 stride_d = 16;
             } else {
                 int m = tj - n_cache;
@@ -751,15 +808,17 @@ void launch_pack_weight(int dtype, const void *src, int rows, int cols, void *ds
 }
 
 void launch_embed_rows(int dtype, const void *embed, const int32_t *tokens, int tok_stride, const int32_t *prefix_len,
-                       RowDesc d, int B, int d_model, int mask_id, int hd, float rope_base, float *x,
+                       RowDesc d, int B, int d_model, int mask_id, int vocab, KvView kv, float rope_base, float *x,
                        int32_t *pos_out, float *rope_cs, hipStream_t st) {
     int rows = B * d.R;
     if (dtype == TIDAR_BF16)
         embed_rows_kernel<bf16_t><<<rows, 256, 0, st>>>((const bf16_t *)embed, tokens, tok_stride, prefix_len, d,
-                                                         d_model, mask_id, hd, rope_base, x, pos_out, rope_cs);
+                                                         d_model, mask_id, vocab, kv, kv.hd, rope_base, x, pos_out,
+                                                         rope_cs);
     else
         embed_rows_kernel<float><<<rows, 256, 0, st>>>((const float *)embed, tokens, tok_stride, prefix_len, d,
-                                                        d_model, mask_id, hd, rope_base, x, pos_out, rope_cs);
+                                                        d_model, mask_id, vocab, kv, kv.hd, rope_base, x, pos_out,
+                                                        rope_cs);
 }
 
 void launch_rmsnorm(int dtype, float *x, const float *part, int S, const void *gain, float eps, int B, int R, int row0,
@@ -869,19 +928,21 @@ void launch_score_loss(const float *ar, const float *diff, int n, float alpha, f
     score_loss_kernel<<<1, 256, 0, st>>>(ar, diff, n, alpha, loss);
 }
 
-void launch_verify_step(const int32_t *y, const int32_t *drafts, int k, int B, int32_t *prefix_len,
-                        int32_t *accepted_len, int32_t *accepted_tokens, int32_t *next_drafts, hipStream_t st) {
-    verify_step_kernel<<<(B + 63) / 64, 64, 0, st>>>(y, drafts, k, B, prefix_len, accepted_len, accepted_tokens,
-                                                     next_drafts);
+void launch_verify_step(const int32_t *y, const int32_t *drafts, int k, int B, int vocab, KvView kv, int seq_base,
+                        int32_t *prefix_len, int32_t *accepted_len, int32_t *accepted_tokens, int32_t *next_drafts,
+                        hipStream_t st) {
+    verify_step_kernel<<<B, 64, 0, st>>>(y, drafts, k, vocab, kv, seq_base, prefix_len, accepted_len, accepted_tokens,
+                                         next_drafts);
 }
 
-void launch_finish_ar(const int32_t *y, int B, int32_t *prefix_len, int32_t *token_out, hipStream_t st) {
-    finish_ar_kernel<<<(B + 63) / 64, 64, 0, st>>>(y, B, prefix_len, token_out);
+void launch_finish_ar(const int32_t *y, const int32_t *token_in, int B, int vocab, KvView kv, int32_t *prefix_len,
+                      int32_t *token_out, hipStream_t st) {
+    finish_ar_kernel<<<(B + 63) / 64, 64, 0, st>>>(y, token_in, B, vocab, kv, prefix_len, token_out);
 }
 
-void launch_finish_prefill(const int32_t *y, int k, int seq, int add_len, int last, int32_t *prefix_len,
-                           int32_t *first_drafts, hipStream_t st) {
-    finish_prefill_kernel<<<1, 64, 0, st>>>(y, k, seq, add_len, last, prefix_len, first_drafts);
+void launch_finish_prefill(const int32_t *y, const int32_t *tokens, int k, int seq, int add_len, int last, int vocab,
+                           KvView kv, int32_t *prefix_len, int32_t *first_drafts, hipStream_t st) {
+    finish_prefill_kernel<<<1, 64, 0, st>>>(y, tokens, k, seq, add_len, last, vocab, kv, prefix_len, first_drafts);
 }
 
 void launch_set_i32(int32_t *p, int n, int32_t v, hipStream_t st) {

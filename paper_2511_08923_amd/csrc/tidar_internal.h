@@ -84,8 +84,24 @@ struct KvView {
     void *v_pages;             // layer base
     const int32_t *page_table;
     int pages_per_seq;
+    int n_pages;               // physical pages per layer: page ids outside [0, n_pages) are never dereferenced
     int n_kv, hd;
 };
+
+// Device-side guards.  The host checks capacity against the caller's length bound only; the kernels read the real
+// prefix length and the page ids from device memory, which a stale bound or a corrupted table can put anywhere.
+// Every kernel therefore works with a prefix length clamped into the table's range (no address is ever formed
+// from the raw value), K/V of a sequence that does not fit or of a page id outside the pool are not stored, and
+// the kernels that finish a call report such a sequence through its outputs (see tidar.h).
+__host__ __device__ inline int kv_capacity(const KvView &kv) { return kv.pages_per_seq * 16; }
+__host__ __device__ inline bool seq_fits(const KvView &kv, int L, int n_new) {
+    return L >= 0 && (long long)L + n_new <= (long long)kv_capacity(kv);
+}
+__host__ __device__ inline int clamp_prefix(const KvView &kv, int L, int n_new) {
+    const int hi = kv_capacity(kv) - n_new;
+    return L < 0 ? 0 : L > hi ? (hi > 0 ? hi : 0) : L;
+}
+__host__ __device__ inline bool page_ok(const KvView &kv, int page) { return (unsigned)page < (unsigned)kv.n_pages; }
 
 __device__ inline size_t k_page_offset(const KvView &kv, int page, int h, int slot, int d) {
     return (((size_t)page * kv.n_kv + h) * 16 + slot) * kv.hd + d;
@@ -117,7 +133,7 @@ void launch_pack_weight(int dtype, const void *src, int rows, int cols, void *ds
                         int tile_stride, hipStream_t st);
 
 void launch_embed_rows(int dtype, const void *embed, const int32_t *tokens, int tok_stride, const int32_t *prefix_len,
-                       RowDesc d, int B, int d_model, int mask_id, int hd, float rope_base,
+                       RowDesc d, int B, int d_model, int mask_id, int vocab, KvView kv, float rope_base,
                        float *x, int32_t *pos_out, float *rope_cs, hipStream_t st);
 
 // x[row] += sum_s part[s][row]; out[row'] = rmsnorm(x[row]) * gain for rows [row0, R) of each sequence.
@@ -163,7 +179,7 @@ size_t attn_partial_floats(int B, int n_kv, int group, int R, int hd, int splits
 // With one split the kernel writes the result to out (row-major [rows][n_q][hd], or, out_af != 0, the A-fragment
 // layout over B * R rows) and launch_attention_combine does nothing; with more it writes per-split partial
 // results to part, which launch_attention_combine folds into out.
-void launch_attention_bf16(const bf16_t *q, KvView kv, int n_pages, const bf16_t *k_scr, const bf16_t *v_scr,
+void launch_attention_bf16(const bf16_t *q, KvView kv, const bf16_t *k_scr, const bf16_t *v_scr,
                            const int32_t *prefix_len, RowDesc d, int B, int n_q, const AttnPlan &p, float *part,
                            bf16_t *out, int out_af, hipStream_t st);
 void launch_attention_combine(const float *part, int B, int R, int n_q, int n_kv, int hd, int splits, bf16_t *out,
@@ -187,9 +203,13 @@ void launch_score_rows(const float *logits, int rows, int vocab, const int32_t *
                        float *ar_out, float *diff_out, hipStream_t st);
 void launch_score_loss(const float *ar, const float *diff, int n, float alpha, float *loss, hipStream_t st);
 
-void launch_verify_step(const int32_t *y, const int32_t *drafts, int k, int B, int32_t *prefix_len,
-                        int32_t *accepted_len, int32_t *accepted_tokens, int32_t *next_drafts, hipStream_t st);
-void launch_finish_ar(const int32_t *y, int B, int32_t *prefix_len, int32_t *token_out, hipStream_t st);
-void launch_finish_prefill(const int32_t *y, int k, int seq, int add_len, int last, int32_t *prefix_len,
-                           int32_t *first_drafts, hipStream_t st);
+// The kernels that finish a call also check what only the device knows (real prefix lengths, page ids, token ids,
+// rows without a token) and report a bad sequence through its outputs.  kv: any layer's view (table and bounds).
+void launch_verify_step(const int32_t *y, const int32_t *drafts, int k, int B, int vocab, KvView kv, int seq_base,
+                        int32_t *prefix_len, int32_t *accepted_len, int32_t *accepted_tokens, int32_t *next_drafts,
+                        hipStream_t st);
+void launch_finish_ar(const int32_t *y, const int32_t *token_in, int B, int vocab, KvView kv, int32_t *prefix_len,
+                      int32_t *token_out, hipStream_t st);
+void launch_finish_prefill(const int32_t *y, const int32_t *tokens, int k, int seq, int add_len, int last, int vocab,
+                           KvView kv, int32_t *prefix_len, int32_t *first_drafts, hipStream_t st);
 void launch_set_i32(int32_t *p, int n, int32_t v, hipStream_t st);

@@ -5,8 +5,6 @@
 #include <new>
 #include <vector>
 
-#include <stdlib.h>
-
 #include "tidar_internal.h"
 
 namespace {
@@ -183,6 +181,7 @@ KvView layer_view(const tidar_config &c, const tidar_kv_cache *kv, int layer) {
     v.v_pages = (char *)kv->v_pages + per_layer * layer;
     v.page_table = kv->page_table;
     v.pages_per_seq = kv->pages_per_seq;
+    v.n_pages = kv->n_pages;
     v.n_kv = c.n_kv_heads;
     v.hd = c.head_dim;
     return v;
@@ -203,14 +202,14 @@ void gemm(tidar_ctx *ctx, const void *a, const void *w, float *out, int M, int N
     }
 }
 
-void attention(tidar_ctx *ctx, const Layout &l, char *ws, KvView kvv, int n_pages, const int32_t *prefix_len,
+void attention(tidar_ctx *ctx, const Layout &l, char *ws, KvView kvv, const int32_t *prefix_len,
                RowDesc d, int B, int max_keys, void *o_out, hipStream_t st) {
     const tidar_config &c = ctx->cfg;
     if (c.dtype == TIDAR_BF16) {
         AttnPlan ap = plan_attention(B, c.n_kv_heads, c.n_q_heads / c.n_kv_heads, d.R, d.nc, max_keys);
         {
             Prof p(ctx, KC_ATTN, st);
-            launch_attention_bf16((const bf16_t *)(ws + l.q), kvv, n_pages, (const bf16_t *)(ws + l.k_scr),
+            launch_attention_bf16((const bf16_t *)(ws + l.q), kvv, (const bf16_t *)(ws + l.k_scr),
                                   (const bf16_t *)(ws + l.v_scr), prefix_len, d, B, c.n_q_heads, ap,
                                   (float *)(ws + l.attn_part), (bf16_t *)o_out, 1, st);
         }
@@ -248,7 +247,8 @@ void forward_rows(tidar_ctx *ctx, const tidar_weights *w, const tidar_kv_cache *
     {
         Prof p(ctx, KC_EMBED, st);
         launch_embed_rows(c.dtype, w->embed, tokens, tok_stride, prefix_len, d, B, c.d_model, c.mask_token_id,
-                          c.head_dim, c.rope_base, x, (int32_t *)(ws + l.pos), (float *)(ws + l.rope_cs), st);
+                          c.vocab, layer_view(c, kv, 0), c.rope_base, x, (int32_t *)(ws + l.pos),
+                          (float *)(ws + l.rope_cs), st);
     }
     int S_prev = 0;   // split count of the partial sums still waiting to be added to the residual stream
     for (int layer = 0; layer < c.n_layers; ++layer) {
@@ -265,7 +265,7 @@ void forward_rows(tidar_ctx *ctx, const tidar_weights *w, const tidar_kv_cache *
             launch_rope_kv(c.dtype, gout, S, (const float *)(ws + l.rope_cs), prefix_len, d, B, c.n_q_heads, kvv,
                            ws + l.q, ws + l.k_scr, ws + l.v_scr, st);
         }
-        attention(ctx, l, ws, kvv, kv->n_pages, prefix_len, d, B, max_keys, ws + l.o, st);
+        attention(ctx, l, ws, kvv, prefix_len, d, B, max_keys, ws + l.o, st);
         gemm(ctx, ws + l.o, w->wo[layer], gout, M, c.d_model, q_dim, false, &S, st);
         {
             Prof p(ctx, KC_RMSNORM, st);
@@ -500,8 +500,8 @@ tidar_status tidar_step(tidar_ctx *ctx, const tidar_weights *w, const tidar_kv_c
                  l, (char *)ws, st);
     {
         Prof p(ctx, KC_VERIFY, st);
-        launch_verify_step((const int32_t *)((char *)ws + l.y), drafts, k, batch, prefix_len, accepted_len,
-                           accepted_tokens, next_drafts, st);
+        launch_verify_step((const int32_t *)((char *)ws + l.y), drafts, k, batch, c.vocab, layer_view(c, kv, 0), 0,
+                           prefix_len, accepted_len, accepted_tokens, next_drafts, st);
     }
     return TIDAR_OK;
 }
@@ -524,7 +524,8 @@ tidar_status tidar_ar_step(tidar_ctx *ctx, const tidar_weights *w, const tidar_k
                  l, (char *)ws, st);
     {
         Prof p(ctx, KC_VERIFY, st);
-        launch_finish_ar((const int32_t *)((char *)ws + l.y), batch, prefix_len, token_out, st);
+        launch_finish_ar((const int32_t *)((char *)ws + l.y), token_in, batch, c.vocab, layer_view(c, kv, 0),
+                         prefix_len, token_out, st);
     }
     return TIDAR_OK;
 }
@@ -571,8 +572,9 @@ tidar_status tidar_prefill(tidar_ctx *ctx, const tidar_weights *w, const tidar_k
                          c0 + d.R, last ? nc - 1 : -1, 1, &pm, 1, 0, lg, l, (char *)ws, st);
             {
                 Prof p(ctx, KC_VERIFY, st);
-                launch_finish_prefill((const int32_t *)((char *)ws + l.y), k, b, nc, last ? 1 : 0, prefix_len,
-                                      first_drafts, st);
+                launch_finish_prefill((const int32_t *)((char *)ws + l.y), prompt + (size_t)b * prompt_stride + c0, k,
+                                      b, nc, last ? 1 : 0, c.vocab, layer_view(c, kv, 0), prefix_len, first_drafts,
+                                      st);
             }
         }
     }
@@ -690,7 +692,7 @@ tidar_status tidar_hybrid_attention(tidar_ctx *ctx, const tidar_kv_cache *kv, in
     if (c.dtype == TIDAR_BF16) {
         {
             Prof p(ctx, KC_ATTN, st);
-            launch_attention_bf16((const bf16_t *)q, kvv, kv->n_pages, (const bf16_t *)wsb,
+            launch_attention_bf16((const bf16_t *)q, kvv, (const bf16_t *)wsb,
                                   (const bf16_t *)(wsb + scr), prefix_len, d, batch, c.n_q_heads, ap,
                                   (float *)(wsb + 2 * scr), (bf16_t *)out, 0, st);
         }
