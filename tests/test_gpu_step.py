@@ -682,3 +682,67 @@ def test_tiny_fp32_continuous_batching_with_per_sequence_block_length(T):
         assert got[b] == want[b][:len(got[b])], b
         assert int(eng.prefix_len[b]) == lens[b] + len(got[b])
     eng.close()
+
+
+# ----------------------------------------------------------------------------- device-side guards
+def test_device_side_guards_report_bad_sequences_without_touching_the_others(T):
+    """What only the device knows is checked by the kernels: a prefix length beyond the page table (the host saw a
+    smaller bound), a page id outside the pool, a token id outside the vocabulary.  The bad sequence of a batch of
+    two is reported through its outputs and keeps its prefix length; the good one decodes exactly as it does
+    alone; the cache pages of the good sequence are untouched by the bad one."""
+    sh = TI.TINY
+    w = TI.make_weights(sh, seed=1)
+    model = O.OracleModel(sh, w)
+    k, P = 4, 40
+    eng = T.Engine(sh, w, dtype=T.TIDAR_F32, max_k=k, max_batch=2, max_seq_len=64)     # capacity 64 tokens
+    prompts = torch.cat([TI.make_prompt(sh, P, seed=11), TI.make_prompt(sh, P, seed=12)])
+    want = model.ar_decode([int(t) for t in prompts[0]], 12)
+
+    def fresh():
+        first, _ = eng.prefill(prompts, k)
+        torch.cuda.synchronize()
+        return first
+
+    # 1. sequence 1 claims a prefix of 62 tokens: 62 + 4 > 64, but the host is told 40
+    first = fresh()
+    eng.prefix_len[1] = 62
+    before = eng.k_pages.clone()
+    a, acc, nxt, _ = eng.step(first, k, hint=P)
+    torch.cuda.synchronize()
+    assert int(a[1]) == 0 and nxt[1].tolist() == [-1] * k and acc[1].tolist() == [-1] * k
+    assert int(eng.prefix_len[1]) == 62
+    assert int(a[0]) >= 1 and int(nxt[0, 0]) == want[int(a[0])]
+    pages1 = eng.page_table[1].long()
+    assert torch.equal(eng.k_pages[:, pages1], before[:, pages1])          # nothing of sequence 1 was stored
+    # 2. a negative prefix length
+    first = fresh()
+    eng.prefix_len[1] = -5
+    a, acc, nxt, _ = eng.step(first, k, hint=P)
+    torch.cuda.synchronize()
+    assert int(a[1]) == 0 and int(eng.prefix_len[1]) == -5 and int(a[0]) >= 1
+    # 3. a page id outside the pool under the positions sequence 1 writes
+    first = fresh()
+    saved = eng.page_table.clone()
+    eng.page_table[1, P // 16] = 10 ** 6
+    a, acc, nxt, _ = eng.step(first, k, hint=P)
+    torch.cuda.synchronize()
+    assert int(a[1]) == 0 and int(eng.prefix_len[1]) == P and int(a[0]) >= 1
+    tok, _ = eng.ar_step(first[:, 0].contiguous(), hint=P + k)
+    torch.cuda.synchronize()
+    assert int(tok[1]) == -1 and int(eng.prefix_len[1]) == P
+    eng.page_table.copy_(saved)
+    # 4. a token id outside the vocabulary among the drafts of sequence 1
+    first = fresh()
+    bad = first.clone()
+    bad[1, 2] = sh.vocab + 7
+    a, acc, nxt, _ = eng.step(bad, k, hint=P)
+    torch.cuda.synchronize()
+    assert int(a[1]) == 0 and int(a[0]) >= 1 and int(nxt[0, 0]) == want[int(a[0])]
+    # 5. the same in a prompt: that sequence's prefill is refused, the other's is not
+    p2 = prompts.clone()
+    p2[1, 7] = -3
+    first, _ = eng.prefill(p2, k)
+    torch.cuda.synchronize()
+    assert eng.prefix_len.tolist() == [P, -1] and first[1].tolist() == [-1] * k
+    assert int(first[0, 0]) == want[0]
+    eng.close()
