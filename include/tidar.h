@@ -54,6 +54,7 @@ typedef enum {
 
 enum { TIDAR_F32 = 0, TIDAR_BF16 = 1 };
 enum { TIDAR_PAGE_SIZE = 16, TIDAR_MAX_K = 16 };
+enum { TIDAR_STATIC_SCRATCH_BYTES = 32 << 20 };   /* scratch of tidar_gemm_static, per GPU, for the life of the process */
 
 typedef struct {
     int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ff, vocab;
@@ -242,6 +243,20 @@ tidar_status tidar_hybrid_attention(tidar_ctx *ctx, const tidar_kv_cache *kv, in
 size_t       tidar_gemm_workspace_bytes(int32_t dtype, int32_t M, int32_t N, int32_t K);
 tidar_status tidar_gemm(tidar_ctx *ctx, const void *a, const void *w_packed, float *out,
                         int32_t M, int32_t N, int32_t K, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * tidar_gemm for callers that cannot allocate or hand over a workspace: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same kernels and the same result as tidar_gemm, but the A-fragment copy
+ * and the split-K partial sums live in a static device array of TIDAR_STATIC_SCRATCH_BYTES (32 MiB) that is part
+ * of the library image on every GPU it runs on; the call allocates nothing, creates no events (the profiling
+ * switch is ignored) and takes no workspace.  Shapes whose tidar_gemm_workspace_bytes exceed the array are rejected
+ * with TIDAR_ENOMEM before anything is enqueued (272 x 4096 x 12288 in bf16 needs 24.5 MiB and fits; 4096 rows of
+ * the same do not); TIDAR_EDEVICE when the current device cannot give the array's address.  All calls on one GPU
+ * share the one array: calls that overlap in time on the same GPU (two streams, two threads) race; calls on one
+ * stream are ordered.  Nothing in the array has to be cleared between calls, whatever an earlier call left there.
+ */
+tidar_status tidar_gemm_static(tidar_ctx *ctx, const void *a, const void *w_packed, float *out,
+                               int32_t M, int32_t N, int32_t K, void *stream);
 
 /*
  * Likelihood of a text in AR mode (paper Section 4.2.2: the causal section alone scores a text the way any

@@ -28,7 +28,8 @@ EXPORTS = ["tidar_create", "tidar_destroy", "tidar_strerror", "tidar_packed_weig
            "tidar_workspace_bytes", "tidar_prefill", "tidar_step", "tidar_ar_step", "tidar_hybrid_attention",
            "tidar_gemm_workspace_bytes", "tidar_gemm", "tidar_profile_enable", "tidar_profile_read",
            "tidar_profile_reset", "tidar_select_block_len", "tidar_set_prefill_chunk", "tidar_score_workspace_bytes",
-           "tidar_score"]
+           "tidar_score", "tidar_gemm_static"]
+STATIC_SCRATCH_BYTES = 32 << 20
 
 
 class TidarError(RuntimeError):
@@ -92,6 +93,8 @@ def _load() -> C.CDLL:
     lib.tidar_gemm_workspace_bytes.restype = sz
     lib.tidar_gemm.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp, sz, vp]
     lib.tidar_gemm.restype = i32
+    lib.tidar_gemm_static.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp]
+    lib.tidar_gemm_static.restype = i32
     lib.tidar_profile_enable.argtypes = [vp, i32]
     lib.tidar_profile_enable.restype = i32
     lib.tidar_profile_read.argtypes = [vp, C.POINTER(C.c_char_p), C.POINTER(C.c_double), C.POINTER(C.c_int64), i32]
@@ -202,6 +205,11 @@ def tidar_gemm(ctx, a: torch.Tensor, w_packed: torch.Tensor, out: torch.Tensor, 
                ws: torch.Tensor) -> None:
     _check(_lib.tidar_gemm(ctx, a.data_ptr(), w_packed.data_ptr(), out.data_ptr(), M, N, K, ws.data_ptr(),
                            ws.numel() * ws.element_size(), _stream()), "tidar_gemm")
+
+
+def tidar_gemm_static(ctx, a: torch.Tensor, w_packed: torch.Tensor, out: torch.Tensor, M: int, N: int, K: int) -> None:
+    _check(_lib.tidar_gemm_static(ctx, a.data_ptr(), w_packed.data_ptr(), out.data_ptr(), M, N, K, _stream()),
+           "tidar_gemm_static")
 
 
 def tidar_profile_enable(ctx, on: bool) -> None:

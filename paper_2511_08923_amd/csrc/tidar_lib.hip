@@ -20,6 +20,35 @@ struct ProfEvent {
 
 }  // namespace
 
+// Scratch of tidar_gemm_static: device memory that belongs to the library image itself, so that the entry point
+// needs no allocation and no workspace argument.  Every GPU the library runs on holds its own copy of the array at
+// its own address for the life of the process.  In host code the array's name is only a handle for the symbol:
+// the address kernels may use is asked for once per device (scratch_address) and kept.
+static __device__ __align__(256) unsigned char scratch[TIDAR_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+void *g_scratch_addr[kMaxDevices] = {};
+
+// Address of `scratch` on the current device; nullptr when there is no usable device.
+void *scratch_address() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    if (!g_scratch_addr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        g_scratch_addr[dev] = p;
+    }
+    return g_scratch_addr[dev];
+}
+}  // namespace
+
 struct tidar_ctx {
     tidar_config cfg;
     int prefill_chunk;
@@ -401,7 +430,7 @@ const char *tidar_strerror(tidar_status s) {
     switch (s) {
         case TIDAR_OK: return "ok";
         case TIDAR_EINVAL: return "invalid argument";
-        case TIDAR_ENOMEM: return "workspace too small";
+        case TIDAR_ENOMEM: return "workspace too small (or, for tidar_gemm_static, the shape needs more than the static scratch)";
         case TIDAR_ECAPACITY: return "KV page table too short for prefix plus new rows";
         case TIDAR_EDEVICE: return "no gfx950 device or HIP error";
         case TIDAR_ESTATE: return "call order violated";
@@ -424,6 +453,7 @@ tidar_status tidar_create(const tidar_config *cfg, tidar_ctx **out) {
     }
     tidar_ctx *c = new (std::nothrow) tidar_ctx();
     if (!c) return TIDAR_ENOMEM;
+    if (n_dev > 0) (void)scratch_address();     // set-up time is the place for the symbol lookup of this device
     c->cfg = *cfg;
     c->prefill_chunk = kDefaultPrefillChunk;
     c->profiling = false;
@@ -728,6 +758,32 @@ tidar_status tidar_gemm(tidar_ctx *ctx, const void *a, const void *w_packed, flo
     int S = 1;
     gemm(ctx, a_frag, w_packed, part, M, N, K, false, &S, st);
     launch_untile_sum(part, S, M, N, out, st);
+    return TIDAR_OK;
+}
+
+tidar_status tidar_gemm_static(tidar_ctx *ctx, const void *a, const void *w_packed, float *out, int32_t M, int32_t N,
+                               int32_t K, void *stream) {
+    if (!ctx || !a || !w_packed || !out || M < 1 || N < 1 || K < 1) return TIDAR_EINVAL;
+    if (N % 16 || K % 8) return TIDAR_EINVAL;
+    const int dtype = ctx->cfg.dtype;
+    if (dtype == TIDAR_BF16 && K % 32) return TIDAR_EINVAL;
+    if (tidar_gemm_workspace_bytes(dtype, M, N, K) > (size_t)TIDAR_STATIC_SCRATCH_BYTES) return TIDAR_ENOMEM;
+    char *base = (char *)scratch_address();     // first call on this device: one symbol lookup, no allocation
+    if (!base) return TIDAR_EDEVICE;
+    hipStream_t st = (hipStream_t)stream;
+    float *part = (float *)(base + align_up(af_elems(M, K) * esize(dtype)));
+    // Nothing in the scratch has to start at zero: pack_act writes every A element of the M real rows, the pad
+    // rows of the last row tile only feed output rows that are never stored, and untile_sum reads exactly the
+    // partial sums this call's GEMM wrote.  What an earlier, larger call left behind is never read as data.
+    launch_pack_act(dtype, a, M, K, base, st);
+    if (dtype == TIDAR_BF16) {
+        GemmPlan gp = plan_gemm_bf16(M, N, K, false);
+        launch_gemm_bf16((const bf16_t *)base, (const bf16_t *)w_packed, part, M, N, K, gp, GEMM_EPI_TILED, st);
+        launch_untile_sum(part, gp.splits, M, N, out, st);
+    } else {
+        launch_gemm_f32((const float *)base, (const float *)w_packed, part, M, N, K, 0, st);
+        launch_untile_sum(part, 1, M, N, out, st);
+    }
     return TIDAR_OK;
 }
 
