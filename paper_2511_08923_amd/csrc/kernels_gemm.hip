@@ -58,9 +58,39 @@ __device__ inline SplitRange split_range(int K, int splits, int split) {
     return r;
 }
 
+// What the fused vocabulary reduction does with output row `row`: perturb its values before the maximum is formed
+// (key, inv_t when noisy) and/or also write its logits to the compact buffer (sel >= 0: row index there).
+struct RowChoice {
+    bool noisy;
+    uint64_t key;
+    float inv_t;
+    int sel;
+};
+__device__ inline RowChoice row_choice(const ChooseArgs &ch, int row, int M) {
+    RowChoice rc;
+    rc.noisy = false;
+    rc.key = 0;
+    rc.inv_t = 1.f;
+    rc.sel = -1;
+    if (ch.n_choose <= 0 || row >= M) return rc;
+    const int b = row / ch.Rh, o = row - b * ch.Rh;
+    if (o < ch.n_choose) {
+        if (ch.sample) {
+            rc.noisy = true;                // causal rows are label shifted: they predict the position after theirs
+            rc.key = noise_key(ch.seed, ch.seq_base + b, ch.pos_rows[(size_t)b * ch.pos_stride + ch.pos_row0 + o] + 1);
+            rc.inv_t = ch.inv_t;
+        }
+        if (ch.sel_logits) rc.sel = b * 2 * ch.n_choose + o;
+    } else if (ch.sel_logits) {
+        const int m = o - ch.n_choose;
+        if (m % ch.mix_stride == 0 && m / ch.mix_stride < ch.n_choose) rc.sel = b * 2 * ch.n_choose + ch.n_choose + m / ch.mix_stride;
+    }
+    return rc;
+}
+
 template <int MTW, int NT>
 __device__ inline void store_tiles(const f32x4 (&acc)[MTW][NT], float *out, int split, int M, int N, int tile0,
-                                   int n_tiles, int mt0, int lane, int out_row_major) {
+                                   int n_tiles, int mt0, int lane, int out_row_major, const ChooseArgs &ch) {
     if (out_row_major == GEMM_EPI_ARGMAX) {
         // lane l holds rows 4*(l/16)+i of a 16-row tile and column l%16 of each of its NT 16-column tiles: the
         // larger of its columns per row, then the 16 lanes of a row group are folded (ties: lowest column)
@@ -73,9 +103,14 @@ __device__ inline void store_tiles(const f32x4 (&acc)[MTW][NT], float *out, int 
             for (int i = 0; i < 4; ++i) {
                 float best = -INFINITY;
                 int bi = (tile0 << 4) + (lane & 15);
+                const int row_i = (mt0 + mt) * 16 + (lane >> 4) * 4 + i;
+                const RowChoice rc = row_choice(ch, row_i, M);
 #pragma unroll
                 for (int j = 0; j < NT; ++j) {
-                    const float v = acc[mt][j][i];
+                    float v = acc[mt][j][i];
+                    const int col = ((tile0 + j) << 4) + (lane & 15);
+                    if (rc.sel >= 0 && tile0 + j < n_tiles) ch.sel_logits[(size_t)rc.sel * N + col] = v;
+                    if (rc.noisy) v = perturbed_logit(v, rc.inv_t, rc.key, (uint32_t)col);
                     if (tile0 + j < n_tiles && v > best) {
                         best = v;
                         bi = ((tile0 + j) << 4) + (lane & 15);
@@ -143,7 +178,8 @@ __device__ inline void store_tiles(const f32x4 (&acc)[MTW][NT], float *out, int 
 template <int MT, int PFK>
 __global__ __launch_bounds__(256) void gemm_bf16_small_kernel(const bf16_t *__restrict__ a,
                                                               const bf16_t *__restrict__ w, float *__restrict__ out,
-                                                              int M, int N, int K, int splits, int out_row_major) {
+                                                              int M, int N, int K, int splits, int out_row_major,
+                                                              ChooseArgs ch) {
     constexpr int NT = 2;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int n_tiles = N >> 4, m_tiles = (M + 15) >> 4;
@@ -203,7 +239,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_small_kernel(const bf16_t *__re
             __builtin_amdgcn_sched_barrier(0);
         }
     }
-    store_tiles<MT, NT>(acc, out, blockIdx.y, M, N, tile0, n_tiles, 0, lane, out_row_major);
+    store_tiles<MT, NT>(acc, out, blockIdx.y, M, N, tile0, n_tiles, 0, lane, out_row_major, ch);
 }
 
 // ------------------------------------------------------------------ 32 < M: 32x32x16 MFMA, A through LDS
@@ -215,7 +251,8 @@ template <int MTA, bool WIDE>
 __global__ __launch_bounds__(256) void gemm_bf16_large_kernel(const bf16_t *__restrict__ a,
                                                               const bf16_t *__restrict__ w, float *__restrict__ out,
                                                               int M, int N, int K, int splits, int epi,
-                                                              int swz_p, int swz_c, int n_pass, int n_colblk) {
+                                                              int swz_p, int swz_c, int n_pass, int n_colblk,
+                                                              ChooseArgs ch) {
     constexpr int NT = 2, KS = 8;
     constexpr bool BIG = WIDE && MTA >= 6;       // the many-row variants: registers go to the accumulators
     constexpr int PFK = BIG ? KS : 2 * KS;       // weight ring depth in k steps: one chunk or two
@@ -431,17 +468,34 @@ __global__ __launch_bounds__(256) void gemm_bf16_large_kernel(const bf16_t *__re
             if (tile_r >= ct_here) continue;      // wave-uniform
             float best = -INFINITY;
             int bi = tile0 * 32 + 4 * lh;
+            const RowChoice rc = row_choice(ch, (mt_base + tile_r) * 32 + lq, M);
+            if (__any(rc.noisy || rc.sel >= 0)) {     // a tile that holds rows a token is taken from (wave-uniform)
 #pragma unroll
-            for (int j = 0; j < NT; ++j)
+                for (int j = 0; j < NT; ++j)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int col = (tile0 + j) * 32 + 8 * (e >> 2) + 4 * lh + (e & 3);
-                    const float v = acc[mt][j][e];
-                    if (col < N && v > best) {
-                        best = v;
-                        bi = col;
+                    for (int e = 0; e < 16; ++e) {
+                        const int col = (tile0 + j) * 32 + 8 * (e >> 2) + 4 * lh + (e & 3);
+                        float v = acc[mt][j][e];
+                        if (rc.sel >= 0 && col < N) ch.sel_logits[(size_t)rc.sel * N + col] = v;
+                        if (rc.noisy) v = perturbed_logit(v, rc.inv_t, rc.key, (uint32_t)col);
+                        if (col < N && v > best) {
+                            best = v;
+                            bi = col;
+                        }
                     }
-                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < NT; ++j)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        const int col = (tile0 + j) * 32 + 8 * (e >> 2) + 4 * lh + (e & 3);
+                        const float v = acc[mt][j][e];
+                        if (col < N && v > best) {
+                            best = v;
+                            bi = col;
+                        }
+                    }
+            }
             const float ob = __shfl_xor(best, 32);
             const int oi = __shfl_xor(bi, 32);
             if (ob > best || (ob == best && oi < bi)) {
@@ -490,14 +544,14 @@ __global__ __launch_bounds__(256) void gemm_bf16_large_kernel(const bf16_t *__re
 
 template <int MT, int PFK>
 void launch_small(const bf16_t *a, const bf16_t *w, float *out, int M, int N, int K, const GemmPlan &p, int row_major,
-                  hipStream_t st) {
+                  hipStream_t st, const ChooseArgs &ch) {
     dim3 grid((N + 127) / 128, p.splits, 1);
-    gemm_bf16_small_kernel<MT, PFK><<<grid, 256, 0, st>>>(a, w, out, M, N, K, p.splits, row_major);
+    gemm_bf16_small_kernel<MT, PFK><<<grid, 256, 0, st>>>(a, w, out, M, N, K, p.splits, row_major, ch);
 }
 
 template <int MTA, bool WIDE>
 void launch_large(const bf16_t *a, const bf16_t *w, float *out, int M, int N, int K, const GemmPlan &p, int epi,
-                  hipStream_t st) {
+                  hipStream_t st, const ChooseArgs &ch) {
     constexpr int CTL = WIDE ? MTA : (MTA == 5) ? 9 : 2 * MTA;
     constexpr int BN = WIDE ? 256 : 128;
     int m_tiles = (M + 31) / 32;
@@ -521,7 +575,7 @@ void launch_large(const bf16_t *a, const bf16_t *w, float *out, int M, int N, in
         if (dev >= 0 && dev < 64) attr_set[dev] = true;
     }
     gemm_bf16_large_kernel<MTA, WIDE><<<grid, 256, SMEM, st>>>(a, w, out, M, N, K, p.splits, epi, swz_p, swz_c, n_pass,
-                                                               n_colblk);
+                                                               n_colblk, ch);
 }
 
 }  // namespace
@@ -613,25 +667,27 @@ GemmPlan plan_gemm_bf16(int M, int N, int K, bool force_single_split) {
 }
 
 void launch_gemm_bf16(const bf16_t *a, const bf16_t *w, float *out, int M, int N, int K, const GemmPlan &p,
-                      int out_row_major, hipStream_t st) {
+                      int out_row_major, hipStream_t st, const ChooseArgs *choose) {
+    ChooseArgs ch = {};
+    if (choose && out_row_major == GEMM_EPI_ARGMAX) ch = *choose;
     if (M <= 32) {
-        if (p.mt == 1) launch_small<1, 16>(a, w, out, M, N, K, p, out_row_major, st);
-        else launch_small<2, 8>(a, w, out, M, N, K, p, out_row_major, st);
+        if (p.mt == 1) launch_small<1, 16>(a, w, out, M, N, K, p, out_row_major, st, ch);
+        else launch_small<2, 8>(a, w, out, M, N, K, p, out_row_major, st, ch);
     } else if (p.wide && p.mt == 8) {
-        launch_large<8, true>(a, w, out, M, N, K, p, out_row_major, st);
+        launch_large<8, true>(a, w, out, M, N, K, p, out_row_major, st, ch);
     } else if (p.wide && p.mt == 7) {
-        launch_large<7, true>(a, w, out, M, N, K, p, out_row_major, st);
+        launch_large<7, true>(a, w, out, M, N, K, p, out_row_major, st, ch);
     } else if (p.wide && p.mt == 6) {
-        launch_large<6, true>(a, w, out, M, N, K, p, out_row_major, st);
+        launch_large<6, true>(a, w, out, M, N, K, p, out_row_major, st, ch);
     } else if (p.wide) {
-        launch_large<5, true>(a, w, out, M, N, K, p, out_row_major, st);
+        launch_large<5, true>(a, w, out, M, N, K, p, out_row_major, st, ch);
     } else if (p.mt == 1) {
-        launch_large<1, false>(a, w, out, M, N, K, p, out_row_major, st);
+        launch_large<1, false>(a, w, out, M, N, K, p, out_row_major, st, ch);
     } else if (p.mt == 2) {
-        launch_large<2, false>(a, w, out, M, N, K, p, out_row_major, st);
+        launch_large<2, false>(a, w, out, M, N, K, p, out_row_major, st, ch);
     } else if (p.mt == 3) {
-        launch_large<3, false>(a, w, out, M, N, K, p, out_row_major, st);
+        launch_large<3, false>(a, w, out, M, N, K, p, out_row_major, st, ch);
     } else {
-        launch_large<5, false>(a, w, out, M, N, K, p, out_row_major, st);
+        launch_large<5, false>(a, w, out, M, N, K, p, out_row_major, st, ch);
     }
 }

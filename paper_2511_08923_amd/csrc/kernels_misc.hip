@@ -367,26 +367,14 @@ __global__ void swiglu_kernel(const float *__restrict__ part, int S, size_t spli
 }
 
 // ------------------------------------------------------------------ vocabulary argmax / Gumbel-max
-// Counter-based noise keyed by (seed, sequence, predicted absolute position, token id): a splitmix-style
-// finaliser over a linear combination of the key fields; 24 bits -> u in (0,1) -> -ln(-ln u).
-__device__ inline uint32_t hash_u24(uint64_t key, uint32_t v) {
-    uint64_t z = key + (uint64_t)(v + 1) * 0xD6E8FEB86659FD93ull;
-    z ^= z >> 30;
-    z *= 0xBF58476D1CE4E5B9ull;
-    z ^= z >> 27;
-    z *= 0x94D049BB133111EBull;
-    z ^= z >> 31;
-    return (uint32_t)(z >> 40);
-}
-
-__global__ void argmax_rows_kernel(const float *__restrict__ logits, int Rh, int vocab, int n_choose,
+// One block per (sequence, row o < n_rows) over materialised logits with Rh rows per sequence.
+__global__ void argmax_rows_kernel(const float *__restrict__ logits, int Rh, int n_rows, int vocab, int n_choose,
                                    const int32_t *__restrict__ pos_rows, int pos_stride, int pos_row0, int seq_base,
                                    int sample, float temperature, uint64_t seed, float beta, int mix_base,
-                                   int mix_stride, int32_t *__restrict__ y) {
-    int row = blockIdx.x;                  // b * Rh + o
-    int b = row / Rh;
-    int o = row - b * Rh;
-    const float *lg = logits + (size_t)row * vocab;
+                                   int mix_stride, int32_t *__restrict__ y, int y_stride) {
+    int b = blockIdx.x / n_rows;
+    int o = blockIdx.x - b * n_rows;
+    const float *lg = logits + ((size_t)b * Rh + o) * vocab;
     bool choose = o < n_choose;            // a row whose token is *taken* (causal logits)
     const float *mix = nullptr;
     if (choose && beta != 1.0f) mix = logits + ((size_t)b * Rh + mix_base + (size_t)o * mix_stride) * vocab;
@@ -395,8 +383,7 @@ __global__ void argmax_rows_kernel(const float *__restrict__ logits, int Rh, int
     float inv_t = 1.f;
     if (noisy) {
         int pos_pred = pos_rows[(size_t)b * pos_stride + pos_row0 + o] + 1;      // causal rows are label shifted
-        key = seed ^ (0x9E3779B97F4A7C15ull * (uint64_t)(pos_pred + 1)) ^
-              (0xC2B2AE3D27D4EB4Full * (uint64_t)(seq_base + b + 1));
+        key = noise_key(seed, seq_base + b, pos_pred);
         inv_t = 1.f / temperature;
     }
     float best = -INFINITY;
@@ -404,10 +391,7 @@ __global__ void argmax_rows_kernel(const float *__restrict__ logits, int Rh, int
     for (int v = threadIdx.x; v < vocab; v += blockDim.x) {
         float val = lg[v];
         if (mix) val = beta * val + (1.f - beta) * mix[v];
-        if (noisy) {
-            float u = ((float)hash_u24(key, (uint32_t)v) + 0.5f) * (1.0f / 16777216.0f);
-            val = val * inv_t + (-logf(-logf(u)));
-        }
+        if (noisy) val = perturbed_logit(val, inv_t, key, (uint32_t)v);
         if (val > best || (val == best && v < best_i)) { best = val; best_i = v; }
     }
 #pragma unroll
@@ -423,7 +407,8 @@ __global__ void argmax_rows_kernel(const float *__restrict__ logits, int Rh, int
     if (threadIdx.x == 0) {
         for (int w = 1; w < (int)(blockDim.x >> 6); ++w)
             if (sb[w] > best || (sb[w] == best && si[w] < best_i)) { best = sb[w]; best_i = si[w]; }
-        y[row] = best_i == 0x7fffffff ? -1 : best_i;     // a row without a single number (all NaN) has no token
+        y[(size_t)b * y_stride + o] = best_i == 0x7fffffff ? -1 : best_i;     // a row without a single number
+                                                                              // (all NaN) has no token
     }
 }
 
@@ -912,11 +897,13 @@ void launch_argmax_groups(const float *part, int M, int G, int32_t *y, hipStream
     argmax_groups_kernel<<<(M + RB - 1) / RB, 1024, 0, st>>>(part, M, G, RB, y);
 }
 
-void launch_argmax_rows(const float *logits, int B, int Rh, int vocab, int n_choose, const int32_t *pos_rows,
-                        int pos_stride, int pos_row0, int seq_base, int sample, float temperature, uint64_t seed,
-                        float beta, int mix_base, int mix_stride, int32_t *y, hipStream_t st) {
-    argmax_rows_kernel<<<B * Rh, 1024, 0, st>>>(logits, Rh, vocab, n_choose, pos_rows, pos_stride, pos_row0, seq_base,
-                                                sample, temperature, seed, beta, mix_base, mix_stride, y);
+void launch_argmax_rows(const float *logits, int B, int Rh, int n_rows, int vocab, int n_choose,
+                        const int32_t *pos_rows, int pos_stride, int pos_row0, int seq_base, int sample,
+                        float temperature, uint64_t seed, float beta, int mix_base, int mix_stride, int32_t *y,
+                        int y_stride, hipStream_t st) {
+    argmax_rows_kernel<<<B * n_rows, 1024, 0, st>>>(logits, Rh, n_rows, vocab, n_choose, pos_rows, pos_stride, pos_row0,
+                                                    seq_base, sample, temperature, seed, beta, mix_base, mix_stride, y,
+                                                    y_stride);
 }
 
 void launch_score_rows(const float *logits, int rows, int vocab, const int32_t *text, int len, int c0, int nc,

@@ -110,6 +110,46 @@ __device__ inline size_t v_page_offset(const KvView &kv, int page, int h, int sl
     return (((size_t)page * kv.n_kv + h) * kv.hd + d) * 16 + slot;
 }
 
+// Counter-based sampling noise (Section 3.2: tokens are *sampled* from the causal logits; the paper fixes no
+// generator).  24 bits keyed by (seed, sequence, predicted absolute position, token id): a splitmix-style finaliser
+// over a linear combination of the key fields; u = (bits + 1/2) / 2^24 in (0, 1); Gumbel noise -ln(-ln u).  Keyed
+// by position, not by step, so one-token decoding and TiDAR decoding draw the same noise for the same token slot.
+__host__ __device__ inline uint64_t noise_key(uint64_t seed, int seq, int pos_pred) {
+    return seed ^ (0x9E3779B97F4A7C15ull * (uint64_t)(pos_pred + 1)) ^ (0xC2B2AE3D27D4EB4Full * (uint64_t)(seq + 1));
+}
+__host__ __device__ inline uint32_t hash_u24(uint64_t key, uint32_t v) {
+    uint64_t z = key + (uint64_t)(v + 1) * 0xD6E8FEB86659FD93ull;
+    z ^= z >> 30;
+    z *= 0xBF58476D1CE4E5B9ull;
+    z ^= z >> 27;
+    z *= 0x94D049BB133111EBull;
+    z ^= z >> 31;
+    return (uint32_t)(z >> 40);
+}
+// logit / T + Gumbel(key, v): one expression for every kernel that samples, so that the fused vocabulary reduction
+// and the reduction over materialised logits choose the same token bit for bit.
+__device__ inline float perturbed_logit(float logit, float inv_t, uint64_t key, uint32_t v) {
+    const float u = ((float)hash_u24(key, v) + 0.5f) * (1.0f / 16777216.0f);
+    return __builtin_fmaf(logit, inv_t, -__logf(-__logf(u)));
+}
+
+// What the LM head's fused vocabulary reduction needs to know about its rows (row = b * Rh + o): the first
+// n_choose rows of every sequence are the rows a token is *taken* from (causal logits); with `sample` their values
+// are perturbed before the maximum is formed.  With sel_logits != nullptr (beta-mixed verification, Section 4.3.3)
+// the logits of those rows and of their mix partners, rows n_choose + i * mix_stride, are also written, compactly:
+// [b][2 * n_choose][N] floats, choose rows first; the mix needs two rows of logits side by side, everything else
+// of the step still leaves the kernel as (maximum, column) pairs only.
+struct ChooseArgs {
+    int Rh, n_choose;
+    const int32_t *pos_rows;      // position id of every row of the forward, [b][pos_stride]
+    int pos_stride, pos_row0, seq_base;
+    int sample;
+    float inv_t;
+    uint64_t seed;
+    float *sel_logits;
+    int mix_stride;
+};
+
 // Profiling hooks (defined in tidar_lib.hip).
 enum KernelClass {
     KC_EMBED = 0, KC_RMSNORM, KC_GEMM, KC_ROPE_KV, KC_ATTN, KC_ATTN_COMBINE, KC_SWIGLU, KC_ARGMAX, KC_VERIFY,
@@ -151,7 +191,7 @@ enum { GEMM_EPI_TILED = 0, GEMM_EPI_ROWMAJOR = 1, GEMM_EPI_SWIGLU = 2, GEMM_EPI_
 inline int gemm_argmax_groups(int M, int N) { return M <= 32 ? (N + 31) / 32 : (N + 63) / 64; }
 void launch_argmax_groups(const float *part, int M, int G, int32_t *y, hipStream_t st);
 void launch_gemm_bf16(const bf16_t *a, const bf16_t *w_packed, float *out, int M, int N, int K, const GemmPlan &p,
-                      int epi, hipStream_t st);
+                      int epi, hipStream_t st, const ChooseArgs *choose = nullptr);
 void launch_gemm_f32(const float *a, const float *w, float *out, int M, int N, int K, int out_row_major,
                      hipStream_t st);
 // plain row-major [M][K] -> A-fragment layout, and tiled partial sums -> plain row-major [M][N]
@@ -190,11 +230,13 @@ void launch_attention_f32(const float *q, KvView kv, const float *k_scr, const f
 
 void launch_swiglu(int dtype, const float *part, int S, int M, int d_ff, void *out, hipStream_t st);
 
-// y[row] = argmax over vocab of (logits or, for the first n_choose rows of each sequence, the sampled /
-// beta-mixed value).  Rows per sequence Rh; causal row i mixes with row mix_base + i*mix_stride when beta != 1.
-void launch_argmax_rows(const float *logits, int B, int Rh, int vocab, int n_choose, const int32_t *pos_rows,
-                        int pos_stride, int pos_row0, int seq_base, int sample, float temperature, uint64_t seed,
-                        float beta, int mix_base, int mix_stride, int32_t *y, hipStream_t st);
+// y[b * y_stride + o] = argmax over vocab of (logits or, for the first n_choose rows of each sequence, the sampled /
+// beta-mixed value), for rows o < n_rows of each sequence.  Rows per sequence in `logits`: Rh; causal row i mixes
+// with row mix_base + i*mix_stride when beta != 1.
+void launch_argmax_rows(const float *logits, int B, int Rh, int n_rows, int vocab, int n_choose,
+                        const int32_t *pos_rows, int pos_stride, int pos_row0, int seq_base, int sample,
+                        float temperature, uint64_t seed, float beta, int mix_base, int mix_stride, int32_t *y,
+                        int y_stride, hipStream_t st);
 
 // Scoring (Section 3.1, Section 4.2.2): log-probability of each row's label under row-major logits of one pass over
 // text positions [c0, c0 + nc) (nc causal rows, then the mask rows), and the objective of one sequence from its

@@ -91,7 +91,8 @@ inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 inline size_t esize(int dtype) { return dtype == TIDAR_BF16 ? 2 : 4; }
 
 struct Layout {
-    size_t pos, rope_cs, x, xn, gemm_out, q, k_scr, v_scr, attn_part, o, h, xh, logits, logits_bytes, y, total;
+    size_t pos, rope_cs, x, xn, gemm_out, q, k_scr, v_scr, attn_part, o, h, xh, logits, logits_bytes, sel_logits, y,
+        total;
     int attn_splits;
 };
 
@@ -114,7 +115,9 @@ size_t gemm_out_floats(const tidar_config &c, int M, int N, int K) {
 }
 
 // Workspace of one forward over B sequences of R rows (n_mask mask rows each), Mh rows through the LM head.
-Layout make_layout(const tidar_config &c, int B, int R, int n_mask, int Mh, int max_keys, bool own_logits) {
+// n_mix: causal rows per sequence whose verification may mix two rows of logits (the decode step: k; else 0).
+Layout make_layout(const tidar_config &c, int B, int R, int n_mask, int Mh, int max_keys, bool own_logits,
+                   int n_mix = 0) {
     Layout l;
     size_t off = 0;
     auto take = [&](size_t bytes) {
@@ -154,6 +157,8 @@ Layout make_layout(const tidar_config &c, int B, int R, int n_mask, int Mh, int 
     l.xh = take(af_elems(Mh > 0 ? Mh : 1, c.d_model) * es);
     l.logits_bytes = own_logits ? (size_t)(Mh > 0 ? Mh : 1) * c.vocab * 4 : 0;
     l.logits = take(l.logits_bytes);
+    // beta-mixed verification through the fused reduction: logits of the k causal rows and their k mix partners only
+    l.sel_logits = take(own_logits && c.dtype == TIDAR_BF16 ? (size_t)B * 2 * n_mix * c.vocab * 4 : 0);
     l.y = take((size_t)(Mh > 0 ? Mh : 1) * 4);
     l.total = off;
     return l;
@@ -334,28 +339,48 @@ void forward_rows(tidar_ctx *ctx, const tidar_weights *w, const tidar_kv_cache *
                           score->diff_out, st);
         return;
     }
-    // Greedy, AR-trusting, nobody asked for the logits: every row's answer is a plain argmax, which the LM head's
-    // epilogue forms per column group; the logits are never written.  (Its partial results fit the logits area:
-    // 8 bytes per row and 32 or 64 columns.)
-    if (c.dtype == TIDAR_BF16 && !logits_dst && !mode->sample && mode->beta == 1.0f && l.logits_bytes > 0) {
+    // Nobody asked for the logits: they are never written.  The LM head's epilogue forms, per row and column group,
+    // the largest value and the lowest column that holds it; for the rows a token is sampled from it perturbs the
+    // values first (same noise, same expression as the reduction over materialised logits).  Beta-mixed
+    // verification needs two rows of logits side by side: the epilogue then also writes the logits of the k causal
+    // rows and of their k mix partners (2k of the k(k+1) rows), which argmax_rows mixes, perturbs and reduces.
+    // (The per-group pairs fit the logits area: 8 bytes per row and 32 or 64 columns.)
+    if (c.dtype == TIDAR_BF16 && !logits_dst && l.logits_bytes > 0) {
         const int G = gemm_argmax_groups(Mh, c.vocab);
+        const bool mix = mode->beta != 1.0f && n_choose > 0 && mix_stride > 0;
+        ChooseArgs ch = {};
+        ch.Rh = Rh;
+        ch.n_choose = n_choose;
+        ch.pos_rows = (const int32_t *)(ws + l.pos);
+        ch.pos_stride = d.R;
+        ch.pos_row0 = head_row0;
+        ch.seq_base = d.seq_base;
+        ch.sample = mix ? 0 : mode->sample;          // mixed rows are perturbed after the mix, by argmax_rows
+        ch.inv_t = 1.f / mode->temperature;
+        ch.seed = mode->seed;
+        ch.sel_logits = mix ? (float *)(ws + l.sel_logits) : nullptr;
+        ch.mix_stride = mix_stride;
         {
             Prof p(ctx, KC_GEMM, st);
             GemmPlan gp = plan_gemm_bf16(Mh, c.vocab, c.d_model, true);
             launch_gemm_bf16((const bf16_t *)(ws + l.xh), (const bf16_t *)w->lm_head, logits, Mh, c.vocab, c.d_model,
-                             gp, GEMM_EPI_ARGMAX, st);
+                             gp, GEMM_EPI_ARGMAX, st, &ch);
         }
         Prof p(ctx, KC_ARGMAX, st);
         launch_argmax_groups(logits, Mh, G, (int32_t *)(ws + l.y), st);
+        if (mix)       // compact rows per sequence: causal row i at i, its partner at n_choose + i
+            launch_argmax_rows(ch.sel_logits, B, 2 * n_choose, n_choose, c.vocab, n_choose, ch.pos_rows, d.R, head_row0,
+                               d.seq_base, mode->sample, mode->temperature, mode->seed, mode->beta, n_choose, 1,
+                               (int32_t *)(ws + l.y), Rh, st);
         return;
     }
     int S = 1;
     gemm(ctx, ws + l.xh, w->lm_head, logits, Mh, c.vocab, c.d_model, true, &S, st);
     {
         Prof p(ctx, KC_ARGMAX, st);
-        launch_argmax_rows(logits, B, Rh, c.vocab, n_choose, (const int32_t *)(ws + l.pos), d.R, head_row0, d.seq_base,
-                           mode->sample, mode->temperature, mode->seed, mode->beta, mix_base, mix_stride,
-                           (int32_t *)(ws + l.y), st);
+        launch_argmax_rows(logits, B, Rh, Rh, c.vocab, n_choose, (const int32_t *)(ws + l.pos), d.R, head_row0,
+                           d.seq_base, mode->sample, mode->temperature, mode->seed, mode->beta, mix_base, mix_stride,
+                           (int32_t *)(ws + l.y), Rh, st);
     }
 }
 
@@ -497,7 +522,7 @@ tidar_status tidar_workspace_bytes(const tidar_ctx *ctx, int32_t batch, int32_t 
     const tidar_config &c = ctx->cfg;
     if (batch < 1 || batch > c.max_batch || k < 1 || k > c.max_k || max_prefix_len < 0) return TIDAR_EINVAL;
     int R = k * (k + 1);
-    Layout a = make_layout(c, batch, R, k * k, batch * R, max_prefix_len + R, true);
+    Layout a = make_layout(c, batch, R, k * k, batch * R, max_prefix_len + R, true, k);
     Layout b = make_layout(c, batch, 1, 0, batch, max_prefix_len + 1, true);
     size_t t = a.total > b.total ? a.total : b.total;
     // prefill passes: a full causal chunk, or a last pass of 1..chunk causal rows plus the mask block
@@ -522,7 +547,7 @@ tidar_status tidar_step(tidar_ctx *ctx, const tidar_weights *w, const tidar_kv_c
     if (batch < 1 || batch > c.max_batch || k < 1 || k > c.max_k || max_prefix_len_hint < 0) return TIDAR_EINVAL;
     if ((int64_t)max_prefix_len_hint + k > (int64_t)kv->pages_per_seq * TIDAR_PAGE_SIZE) return TIDAR_ECAPACITY;
     RowDesc d = step_desc(k);
-    Layout l = make_layout(c, batch, d.R, k * k, batch * d.R, max_prefix_len_hint + d.R, logits_out == nullptr);
+    Layout l = make_layout(c, batch, d.R, k * k, batch * d.R, max_prefix_len_hint + d.R, logits_out == nullptr, k);
     if (l.total > ws_bytes) return TIDAR_ENOMEM;
     hipStream_t st = (hipStream_t)stream;
     // causal row i is label shifted and judges draft i+1; with beta != 1 it is mixed with slot 0 of block i

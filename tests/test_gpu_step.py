@@ -4,7 +4,8 @@ import torch
 
 import tidar_inputs as TI
 from oracle import tidar_oracle as O
-from gpu_util import load_oracle_state_into_engine, near_tie_mismatches
+from gpu_util import (StepParity, load_oracle_state_into_engine, mismatch_rows, near_tie_mismatches,
+                      step_outputs_match_within_margin)
 
 pytestmark = pytest.mark.gpu
 
@@ -211,12 +212,29 @@ def small(T):
     return eng, model
 
 
+@pytest.fixture(scope="module")
+def small_unrounded():
+    """The plain fp64 oracle on the same bf16-valued weights, no rounding points: every bf16 step test also reports
+    its distance to this one."""
+    return O.OracleModel(TI.SMALL_GQA, TI.make_weights(TI.SMALL_GQA, seed=3, dtype=torch.bfloat16))
+
+
+def copy_state(st):
+    return O.State([t.clone() for t in st.k], [t.clone() for t in st.v], st.L, st.seq_id)
+
+
+def dev_out(eng, a, acc, nxt, b=0):
+    return int(a[b]), acc[b].tolist(), nxt[b].tolist(), int(eng.prefix_len[b])
+
+
 LOGIT_TOL = 2e-2
 
 
 @pytest.mark.parametrize("k", [4, 8, 16])
-def test_small_bf16_teacher_forced_steps(T, small, k):
-    """bf16 path against the bf16-faithful oracle, each step started from the oracle's state and drafts."""
+def test_small_bf16_teacher_forced_steps(T, small, small_unrounded, k):
+    """bf16 path against the bf16-faithful oracle, each step started from the oracle's state and drafts.  Tokens,
+    acceptance length and the new prefix length are compared exactly unless a near-tie row is one of the rows the
+    step's outputs depend on (see StepParity)."""
     eng, model = small
     sh = TI.SMALL_GQA
     P = 300 if k == 16 else 70
@@ -227,41 +245,34 @@ def test_small_bf16_teacher_forced_steps(T, small, k):
     torch.cuda.synchronize()
     err = float((lg[0].cpu().double() - lg_o).abs().max())
     assert err < LOGIT_TOL
-    mis, bad = near_tie_mismatches(lg[0].cpu().argmax(-1), lg_o, err)
-    assert bad == 0
+    rows, bad = mismatch_rows(lg[0].cpu().argmax(-1), lg_o, err)
+    assert bad == 0 and len(rows) <= 3      # near ties are common among the mask rows of an untrained model
+    for i in range(k):                     # row 0 of the returned logits gives first[0], mask slot i row 1 + i
+        if (0 if i == 0 else 1 + i) not in rows:
+            assert int(first[0, i]) == d_o[i]
     for l in range(sh.n_layers):           # prefill cache within bf16 rounding of the oracle's
         kk, vv = eng.read_cache(l, 0, P)
         assert float((kk.cpu().double() - st.k[l][:P]).abs().max()) < 4e-2
         assert float((vv.cpu().double() - st.v[l][:P]).abs().max()) < 4e-2
-    total_mis = 0
+    par = StepParity(f"small-gqa k={k}")
     for step in range(4):
         print(f"small bf16 k={k} step {step}", flush=True)
         load_oracle_state_into_engine(eng, st)
         L = st.L
         drafts = list(d_o)
         if step % 2 == 1:                  # every other step: force a long acceptance with oracle-known tokens
-            probe = model.new_state(512)
-            probe.L = st.L
-            probe.k, probe.v = [t.clone() for t in st.k], [t.clone() for t in st.v]
-            _, _, _, plg = model.tidar_step(probe, drafts)
+            _, _, _, plg = model.tidar_step(copy_state(st), drafts)
             for i in range(1, k // 2):
                 drafts[i] = int(plg[i - 1].argmax())
+        _, _, _, lg_u = small_unrounded.tidar_step(copy_state(st), drafts)
         a_o, acc_o, nxt_o, lg_o = model.tidar_step(st, drafts)
         a, acc, nxt, lg = eng.step(torch.tensor([drafts], dtype=torch.int32, device="cuda"), k, hint=L,
                                    want_logits=True)
         torch.cuda.synchronize()
-        err = float((lg[0].cpu().double() - lg_o).abs().max())
-        assert err < LOGIT_TOL, err
-        mis, bad = near_tie_mismatches(lg[0].cpu().argmax(-1), lg_o, err)
-        assert bad == 0, (mis, bad, err)
-        total_mis += mis
-        print(f"  max logit err {err:.2e}, near-tie rows {mis}", flush=True)
-        if mis == 0:
-            assert int(a[0]) == a_o
-            assert acc[0, :a_o].tolist() == acc_o
-            assert nxt[0].tolist() == nxt_o
-            assert int(eng.prefix_len[0]) == st.L
+        par.check(k, lg[0].cpu(), dev_out(eng, a, acc, nxt), lg_o, (a_o, acc_o, nxt_o, st.L), LOGIT_TOL,
+                  unrounded_logits=lg_u)
         d_o = nxt_o
+    par.report(min_exact=3)
 
 
 @pytest.mark.parametrize("k", [1, 4, 16])
@@ -302,6 +313,122 @@ def test_bf16_fused_vocab_reduction_equals_logits_path(T, small, k):
     assert int(t1[0]) == int(t2[0]) == int(lg[0].argmax())
 
 
+@pytest.mark.parametrize("k", [2, 4, 16])
+def test_bf16_fused_vocab_reduction_against_the_oracle(T, small, k):
+    """The production path against the oracle directly: greedy steps that ask for no logits take the LM head's
+    fused per-group argmax (nothing but token ids leaves the device).  Teacher-forced from the oracle's state;
+    every token that surfaces (acceptance length, accepted tokens, next drafts, first drafts of the prefill) must be
+    the oracle's or lose to it by less than twice the stated tolerance in the oracle's own logits (k = 2: the
+    narrow GEMM kernel, 6 rows; 4, 16: the wide one)."""
+    eng, model = small
+    sh = TI.SMALL_GQA
+    P = 120
+    prompt = TI.make_prompt(sh, P, seed=170 + k)
+    st = model.new_state(512)
+    d_o, lg_o = model.prefill(st, [int(t) for t in prompt[0]], k)
+    first, none = eng.prefill(prompt, k)
+    torch.cuda.synchronize()
+    assert none is None
+    for i in range(k):
+        row = 0 if i == 0 else 1 + i
+        if int(first[0, i]) != d_o[i]:
+            assert float(lg_o[row, d_o[i]] - lg_o[row, int(first[0, i])]) < 2 * LOGIT_TOL, (i, first[0].tolist(), d_o)
+    n_exact = 0
+    steps = 6
+    for step in range(steps):
+        load_oracle_state_into_engine(eng, st)
+        L = st.L
+        drafts = list(d_o)
+        if step % 2 == 1:                  # force a longer acceptance with oracle-known tokens
+            _, _, _, plg = model.tidar_step(copy_state(st), drafts)
+            for i in range(1, max(2, k // 2)):
+                if i < k:
+                    drafts[i] = int(plg[i - 1].argmax())
+        a_o, acc_o, nxt_o, lg_o = model.tidar_step(st, drafts)
+        a, acc, nxt, none = eng.step(torch.tensor([drafts], dtype=torch.int32, device="cuda"), k, hint=L)
+        torch.cuda.synchronize()
+        assert none is None
+        n_exact += step_outputs_match_within_margin(k, drafts, dev_out(eng, a, acc, nxt), (a_o, acc_o, nxt_o, st.L),
+                                                    lambda r: lg_o[r], LOGIT_TOL)
+        d_o = nxt_o
+    print(f"  fused argmax path k={k}: {n_exact} of {steps} steps exactly equal to the oracle", flush=True)
+    assert n_exact >= steps - 2
+    # the one-token step's fused reduction (a single row)
+    load_oracle_state_into_engine(eng, st)
+    tok_o, lg1 = model.ar_step(st, d_o[0])
+    tok, _ = eng.ar_step(torch.tensor([d_o[0]], dtype=torch.int32, device="cuda"), hint=st.L)
+    torch.cuda.synchronize()
+    if int(tok[0]) != tok_o:
+        assert float(lg1[0, tok_o] - lg1[0, int(tok[0])]) < 2 * LOGIT_TOL
+
+
+@pytest.mark.parametrize("k,sample,beta", [(8, True, 1.0), (16, True, 1.0), (2, True, 1.0), (8, False, 0.0),
+                                           (16, False, 0.25), (16, True, 0.25), (4, False, 0.25), (1, True, 1.0)])
+def test_bf16_fused_sampling_and_beta_mix_against_the_oracle(T, small, k, sample, beta):
+    """Temperature-1 seeded sampling and beta-mixed verification (Section 4.3.3) through the production path: no
+    logits requested, the perturbation happens in the LM head's epilogue, the mix over the logits of 2k rows only.
+    Teacher-forced against the bf16-faithful oracle; a surfaced token may differ from the oracle's only where it
+    loses by less than twice the stated tolerance in the oracle's own decision scores (logits / T + noise for the
+    sampled causal rows, the beta-mix for the mixed ones).  The same steps with logits requested (reduction over
+    materialised logits) must give the same tokens bit for bit."""
+    eng, model = small
+    sh = TI.SMALL_GQA
+    P = 100
+    seed = 1000 + 17 * k
+    prompt = TI.make_prompt(sh, P, seed=270 + k)
+    omode = O.Mode(sample=sample, temperature=1.0, seed=seed, beta=beta)
+    gmode = T.make_mode(sample=sample, temperature=1.0, seed=seed, beta=beta)
+    st = model.new_state(512)
+    d_o, _ = model.prefill(st, [int(t) for t in prompt[0]], k, omode)
+    n_exact, steps = 0, 5
+    for step in range(steps):
+        load_oracle_state_into_engine(eng, st)
+        L = st.L
+        drafts = list(d_o)
+        if step % 2 == 1 and k > 1:        # drafts the oracle's verifier accepts for a while
+            a_p, _, n_p, _ = model.tidar_step(copy_state(st), drafts, omode)
+            while a_p < max(2, k // 2) and a_p < k:
+                drafts[a_p] = n_p[0]
+                a_p, _, n_p, _ = model.tidar_step(copy_state(st), drafts, omode)
+        a_o, acc_o, nxt_o, lg_o = model.tidar_step(st, drafts, omode)
+
+        def scores(r):
+            sc = lg_o[r]
+            if r < k:
+                if beta != 1.0:
+                    sc = beta * sc + (1.0 - beta) * lg_o[k + r * k]
+                if sample:
+                    sc = sc / 1.0 + torch.from_numpy(O.gumbel_noise(seed, 0, L + r + 1, sh.vocab))
+            return sc
+
+        dd = torch.tensor([drafts], dtype=torch.int32, device="cuda")
+        a, acc, nxt, none = eng.step(dd, k, hint=L, mode=gmode)
+        torch.cuda.synchronize()
+        assert none is None
+        got = dev_out(eng, a, acc, nxt)
+        n_exact += step_outputs_match_within_margin(k, drafts, got, (a_o, acc_o, nxt_o, st.L), scores, LOGIT_TOL)
+        eng.prefix_len[:1].fill_(L)
+        a2, acc2, nxt2, lg = eng.step(dd, k, hint=L, mode=gmode, want_logits=True)
+        torch.cuda.synchronize()
+        assert dev_out(eng, a2, acc2, nxt2) == got, (step, got, dev_out(eng, a2, acc2, nxt2))
+        d_o = nxt_o
+    print(f"  fused k={k} sample={sample} beta={beta}: {n_exact} of {steps} steps exactly equal to the oracle", flush=True)
+    assert n_exact >= steps - 2
+    if sample:                             # the one-token step samples through the same epilogue
+        load_oracle_state_into_engine(eng, st)
+        L = st.L
+        tok_o, lg1 = model.ar_step(st, d_o[0], omode)
+        tin = torch.tensor([d_o[0]], dtype=torch.int32, device="cuda")
+        tok, _ = eng.ar_step(tin, hint=L, mode=gmode)
+        torch.cuda.synchronize()
+        pert = lg1[0] + torch.from_numpy(O.gumbel_noise(seed, 0, L + 1, sh.vocab))
+        assert int(tok[0]) == tok_o or float(pert[tok_o] - pert[int(tok[0])]) < 2 * LOGIT_TOL
+        eng.prefix_len[:1].fill_(L)
+        tok2, _ = eng.ar_step(tin, hint=L, mode=gmode, want_logits=True)
+        torch.cuda.synchronize()
+        assert int(tok2[0]) == int(tok[0])
+
+
 @pytest.mark.parametrize("chunk", [None, 1024])
 def test_small_bf16_long_prompt_one_and_two_passes(T, chunk):
     """A 1100-token prompt against the oracle's single pass.  At the default prefill chunk: one pass of 1100 causal
@@ -319,10 +446,11 @@ def test_small_bf16_long_prompt_one_and_two_passes(T, chunk):
     torch.cuda.synchronize()
     err = float((lg[0].cpu().double() - lg_o).abs().max())
     assert err < LOGIT_TOL, err
-    mis, bad = near_tie_mismatches(lg[0].cpu().argmax(-1), lg_o, err)
-    assert bad == 0
-    if mis == 0:
-        assert first[0].tolist() == d_o
+    rows, bad = mismatch_rows(lg[0].cpu().argmax(-1), lg_o, err)
+    assert bad == 0 and len(rows) <= 3      # near ties are common among the mask rows of an untrained model
+    for i in range(k):
+        if (0 if i == 0 else 1 + i) not in rows:
+            assert int(first[0, i]) == d_o[i]
     assert int(eng.prefix_len[0]) == P
     for l in range(sh.n_layers):
         kk, vv = eng.read_cache(l, 0, P)
@@ -487,18 +615,12 @@ def test_8b_shape_two_layers_one_step_vs_oracle(T):
     print("8b-shape device step ...", flush=True)
     a, acc, nxt, lg = eng.step(torch.tensor([drafts], dtype=torch.int32, device="cuda"), k, hint=L, want_logits=True)
     torch.cuda.synchronize()
-    lg = lg[0].cpu().double()
-    err = float((lg - lg_o).abs().max())
-    rms = float((lg - lg_o).pow(2).mean().sqrt())
+    par = StepParity("8b-shape 2 layers")
+    err, rms, rows = par.check(k, lg[0].cpu(), dev_out(eng, a, acc, nxt), lg_o, (a_o, acc_o, nxt_o, L + a_o),
+                               max(LOGIT_TOL, 1.5 * floor_max), rms_tol=max(LOGIT_TOL / 4, 1.5 * floor_rms))
     print(f"  device vs oracle: max {err:.3e} rms {rms:.3e}; oracle fp32 vs fp64: max {floor_max:.3e} rms "
-          f"{floor_rms:.3e}", flush=True)
-    assert err < max(LOGIT_TOL, 1.5 * floor_max), (err, floor_max)
-    assert rms < max(LOGIT_TOL / 4, 1.5 * floor_rms), (rms, floor_rms)
-    mis, bad = near_tie_mismatches(lg.argmax(-1), lg_o, err)
-    print(f"  near-tie rows {mis}", flush=True)
-    assert bad == 0
-    if mis == 0:
-        assert int(a[0]) == a_o and nxt[0].tolist() == nxt_o
+          f"{floor_rms:.3e}; near-tie rows {len(rows)}", flush=True)
+    par.report(min_exact=0)
     eng.close()
 
 
@@ -522,6 +644,7 @@ def test_1p5b_shape_two_layers_prefill_and_steps_vs_oracle(T):
     assert err < 3e-2      # logit std is 0.78 here (d_model 1536); see the 8B-shape test for the bf16 noise floor
     mis, bad = near_tie_mismatches(lg[0].cpu().argmax(-1), lg_o, err)
     assert bad == 0
+    par = StepParity("1.5b-shape 2 layers")
     for step in range(2):
         load_oracle_state_into_engine(eng, st)
         L = st.L
@@ -530,13 +653,10 @@ def test_1p5b_shape_two_layers_prefill_and_steps_vs_oracle(T):
         a, acc, nxt, lg = eng.step(torch.tensor([drafts], dtype=torch.int32, device="cuda"), k, hint=L,
                                    want_logits=True)
         torch.cuda.synchronize()
-        err = float((lg[0].cpu().double() - lg_o).abs().max())
-        mis, bad = near_tie_mismatches(lg[0].cpu().argmax(-1), lg_o, err)
-        print(f"  step {step}: max logit err {err:.2e}, near-tie rows {mis}", flush=True)
-        assert err < 3e-2 and bad == 0
-        if mis == 0:
-            assert int(a[0]) == a_o and nxt[0].tolist() == nxt_o and acc[0, :a_o].tolist() == acc_o
+        err, rms, rows = par.check(k, lg[0].cpu(), dev_out(eng, a, acc, nxt), lg_o, (a_o, acc_o, nxt_o, st.L), 3e-2)
+        print(f"  step {step}: max logit err {err:.2e}, near-tie rows {len(rows)}", flush=True)
         d_o = nxt_o
+    par.report(min_exact=1)
     eng.close()
 
 
@@ -564,18 +684,11 @@ def test_small_bf16_batched_steps_match_oracle(T, B, k):
     a, acc, nxt, lg = eng.step(torch.tensor(drafts_all, dtype=torch.int32, device="cuda"), k, hint=hint,
                                want_logits=True)
     torch.cuda.synchronize()
-    n_mis = 0
+    par = StepParity(f"batched B={B} k={k}")
     for b in range(B):
         a_o, acc_o, nxt_o, lg_o = want[b]
-        err = float((lg[b].cpu().double() - lg_o).abs().max())
-        assert err < LOGIT_TOL, (b, err)
-        mis, bad = near_tie_mismatches(lg[b].cpu().argmax(-1), lg_o, err)
-        assert bad == 0
-        n_mis += mis
-        if mis == 0:
-            assert int(a[b]) == a_o and nxt[b].tolist() == nxt_o and acc[b, :a_o].tolist() == acc_o
-            assert int(eng.prefix_len[b]) == states[b].L
-    print(f"  batched B={B} k={k}: near-tie rows {n_mis}", flush=True)
+        par.check(k, lg[b].cpu(), dev_out(eng, a, acc, nxt, b), lg_o, (a_o, acc_o, nxt_o, states[b].L), LOGIT_TOL)
+    par.report(min_exact=B - 1)
     # batched AR step on the same engine
     toks = nxt[:, 0].contiguous()
     hint = max(s.L for s in states) + k
