@@ -242,6 +242,229 @@ __global__ __launch_bounds__(256) void gemm_bf16_small_kernel(const bf16_t *__re
     store_tiles<MT, NT>(acc, out, blockIdx.y, M, N, tile0, n_tiles, 0, lane, out_row_major, ch);
 }
 
+// ------------------------------------------------------------------ M <= 4: the same, its producer folded in
+// The A operand is built by the workgroup itself (see FuseArgs) into LDS as plain bf16 rows of its share of K; a
+// lane's fragment is then one 16-byte LDS read (lanes of rows that do not exist take zeros).  W streams through the
+// same register ring, whose first loads are in flight while the prologue runs.
+template <int FUSE>
+__global__ __launch_bounds__(256) void gemm_bf16_small_fused_kernel(FuseArgs f, const bf16_t *__restrict__ w,
+                                                                    float *__restrict__ out, int M, int N, int K,
+                                                                    int splits, int epi) {
+    constexpr int NT = 2, PFK = 16, MT = 1;
+    extern __shared__ __attribute__((aligned(16))) unsigned char fused_smem[];
+    bf16_t *lds_a = reinterpret_cast<bf16_t *>(fused_smem);           // [M][kr]
+    __shared__ float red[4][kFuseMaxRows];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n_tiles = N >> 4;
+    const SplitRange sr = split_range(K, splits, blockIdx.y);
+    const int k0 = sr.q0 * 32, kr = max(sr.q1 - sr.q0, 0) * 32;
+    const int tile0 = (blockIdx.x * 4 + wave) * NT;
+    const __amdgpu_buffer_rsrc_t rw = make_rsrc(w, (size_t)((N + 31) / 32) * 32 * K * 2);
+    const int t32 = (N + 31) >> 5;
+    const int n = lane & 15, g = lane >> 4;
+    int w_off[NT];
+#pragma unroll
+    for (int j = 0; j < NT; ++j)
+        w_off[j] = (tile0 + j < n_tiles)
+                       ? ((((g >> 1) * t32 + ((tile0 + j) >> 1)) * 64) + (g & 1) * 32 + ((tile0 + j) & 1) * 16 + n) * 16
+                       : OOB;
+    const int w_step = 2 * t32 * 1024;
+    auto ld_w = [&](int j, int q) {
+        return buf_load(rw, (q < sr.q1 && w_off[j] != OOB) ? w_off[j] + q * w_step : OOB);
+    };
+    // Loads return in order: the ring's first loads (for a short share of K: all of the workgroup's weights) are
+    // issued *behind* the prologue's loads, which come from L2 and the memory-side cache and are back long before
+    // the weights; the prologue's arithmetic then runs while the weights stream in.
+    bf16x8 wbuf[PFK][NT];
+    auto fill_ring = [&]() __attribute__((always_inline)) {
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int s = 0; s < PFK; ++s)
+#pragma unroll
+            for (int j = 0; j < NT; ++j) wbuf[s][j] = ld_w(j, sr.q0 + s);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+    if (FUSE == GEMM_FUSE_NORM) {
+        // thread t holds columns 4 (t + 256 j) .. +3 of every row.  All loads of a row (the residual piece and up
+        // to eight partial sums per piece) are issued before the first is used: one round trip per row, not one
+        // per split.
+        constexpr int KP = kFuseMaxK / 1024, SB = 8;
+        float4 v[kFuseMaxRows][KP];
+        float ss[kFuseMaxRows];
+#pragma unroll
+        for (int r = 0; r < kFuseMaxRows; ++r) {
+            ss[r] = 0.f;
+#pragma unroll
+            for (int j = 0; j < KP; ++j) v[r][j] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (r >= M) continue;
+#pragma unroll
+            for (int j = 0; j < KP; ++j) {
+                const int c = 4 * (tid + 256 * j);
+                if (c < K) v[r][j] = *(const float4 *)(f.x_in + (size_t)r * K + c);
+            }
+            for (int sp0 = 0; sp0 < f.S; sp0 += SB) {
+                float4 q[SB][KP];
+#pragma unroll
+                for (int u = 0; u < SB; ++u)
+#pragma unroll
+                    for (int j = 0; j < KP; ++j) {
+                        const int c = min(4 * (tid + 256 * j), K - 4);            // clamped: always a real address
+                        q[u][j] = *(const float4 *)(f.part + pt_index(c, r, M) +
+                                                    (size_t)min(sp0 + u, f.S - 1) * f.split_stride);
+                    }
+#pragma unroll
+                for (int u = 0; u < SB; ++u)                  // in split order, as the stand-alone kernel sums
+#pragma unroll
+                    for (int j = 0; j < KP; ++j)
+                        if (sp0 + u < f.S && 4 * (tid + 256 * j) < K) {
+                            v[r][j].x += q[u][j].x; v[r][j].y += q[u][j].y;
+                            v[r][j].z += q[u][j].z; v[r][j].w += q[u][j].w;
+                        }
+            }
+#pragma unroll
+            for (int j = 0; j < KP; ++j)
+                ss[r] += v[r][j].x * v[r][j].x + v[r][j].y * v[r][j].y + v[r][j].z * v[r][j].z + v[r][j].w * v[r][j].w;
+        }
+        fill_ring();
+#pragma unroll
+        for (int r = 0; r < kFuseMaxRows; ++r) {
+            float t = ss[r];
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) t += __shfl_xor(t, o);
+            if (lane == 0) red[wave][r] = t;
+        }
+        __syncthreads();
+        const bool writer = blockIdx.x == 0 && blockIdx.y == 0;
+#pragma unroll
+        for (int r = 0; r < kFuseMaxRows; ++r) {
+            if (r >= M) continue;
+            const float tot = ((red[0][r] + red[1][r]) + red[2][r]) + red[3][r];
+            const float rs = rsqrtf(tot / (float)K + f.eps);
+#pragma unroll
+            for (int j = 0; j < KP; ++j) {
+                const int c = 4 * (tid + 256 * j);
+                if (c >= K) continue;
+                const float4 a = v[r][j];
+                if (writer) *(float4 *)(f.x_out + (size_t)r * K + c) = a;
+                if (c >= k0 && c < k0 + kr) {
+                    const bf16x4 gn = *(const bf16x4 *)(f.gain + c);
+                    const bf16x4 o = {(bf16_t)(a.x * rs * (float)gn[0]), (bf16_t)(a.y * rs * (float)gn[1]),
+                                      (bf16_t)(a.z * rs * (float)gn[2]), (bf16_t)(a.w * rs * (float)gn[3])};
+                    *(bf16x4 *)(lds_a + (size_t)r * kr + (c - k0)) = o;
+                }
+            }
+        }
+    } else {
+        // One item = four head-dim values of one (row, head) of this workgroup's share of K = n_q * 128.  The
+        // threads that the items leave over share an item's splits (TPI threads per item, sixteen splits loaded
+        // together: one or two round trips to memory instead of one per split).  The fold is the online form:
+        // every split keeps an integral reference, so moving the running reference scales by an exact power of
+        // two and the order of the rescales leaves no trace; partial folds of an item meet in LDS in thread order.
+        constexpr int SB = 16;
+        const int group = f.n_q / f.n_kv, F = group * f.R, per_row = kr >> 2;
+        const int items = M * per_row;
+        int tpi = 1;
+        while (tpi < 8 && items * tpi * 2 <= 256) tpi *= 2;
+        __shared__ float fold[256][6];
+        const int part_i = tid % tpi;
+        for (int it0 = 0; it0 < items; it0 += 256 / tpi) {               // one round when the items fit (uniform)
+        const int item = it0 + tid / tpi;
+        float mrun = -INFINITY, den = 0.f;
+        float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
+        int r = 0, kk = k0;
+        if (item < items) {
+            r = item / per_row;
+            kk = k0 + 4 * (item - r * per_row);
+            const int head = kk >> 7, d0 = kk & 127;
+            const int b = r / f.R, rr = r - b * f.R;
+            const int kvh = head / group, hq = head - kvh * group;
+            const size_t base = ((size_t)b * f.n_kv + kvh) * f.a_splits;
+            const int fr = hq * f.R + rr;
+            const int per_t = (f.a_splits + tpi - 1) / tpi;
+            const int s_lo = part_i * per_t, s_hi = min(f.a_splits, s_lo + per_t);
+            for (int sp0 = s_lo; sp0 < s_hi; sp0 += SB) {
+                float m[SB], l[SB];
+                float4 o[SB];
+#pragma unroll
+                for (int u = 0; u < SB; ++u) {
+                    const size_t pi = (base + min(sp0 + u, f.a_splits - 1)) * F + fr;
+                    m[u] = f.mpart[pi];
+                    l[u] = f.lpart[pi];
+                    o[u] = *(const float4 *)(f.opart + pi * 128 + d0);
+                }
+                float mc = mrun;
+#pragma unroll
+                for (int u = 0; u < SB; ++u)
+                    if (sp0 + u < s_hi) mc = fmaxf(mc, m[u]);
+                if (mc == -INFINITY) continue;                              // nothing but empty splits so far
+                const float sc = exp2f(mrun - mc);                          // 0 when mrun is still -inf
+                num.x *= sc; num.y *= sc; num.z *= sc; num.w *= sc;
+                den *= sc;
+                mrun = mc;
+#pragma unroll
+                for (int u = 0; u < SB; ++u) {
+                    if (sp0 + u >= s_hi || m[u] == -INFINITY) continue;     // absent or empty split
+                    const float wgt = exp2f(m[u] - mrun);
+                    num.x += wgt * o[u].x; num.y += wgt * o[u].y; num.z += wgt * o[u].z; num.w += wgt * o[u].w;
+                    den += wgt * l[u];
+                }
+            }
+        }
+        if (it0 == 0) fill_ring();
+        if (tpi > 1) {
+            __syncthreads();                                               // the previous round's folds were read
+            fold[tid][0] = mrun; fold[tid][1] = den;
+            fold[tid][2] = num.x; fold[tid][3] = num.y; fold[tid][4] = num.z; fold[tid][5] = num.w;
+            __syncthreads();
+            if (item < items && part_i == 0) {
+                for (int t = 1; t < tpi; ++t) {
+                    const float *o = fold[tid + t];
+                    if (o[0] == -INFINITY) continue;
+                    const float mc = fmaxf(mrun, o[0]);
+                    const float sa = exp2f(mrun - mc), sb = exp2f(o[0] - mc);
+                    num.x = num.x * sa + o[2] * sb; num.y = num.y * sa + o[3] * sb;
+                    num.z = num.z * sa + o[4] * sb; num.w = num.w * sa + o[5] * sb;
+                    den = den * sa + o[1] * sb;
+                    mrun = mc;
+                }
+            }
+        }
+        if (item < items && part_i == 0) {
+            const float inv = 1.f / den;
+            const bf16x4 o = {(bf16_t)(num.x * inv), (bf16_t)(num.y * inv), (bf16_t)(num.z * inv), (bf16_t)(num.w * inv)};
+            *(bf16x4 *)(lds_a + (size_t)r * kr + (kk - k0)) = o;
+        }
+        }
+    }
+    __syncthreads();
+
+    f32x4 acc[MT][NT];
+#pragma unroll
+    for (int j = 0; j < NT; ++j) acc[0][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    // A fragment of k step q: lane (row n, k slots 8g .. 8g+7)
+    const bf16_t *a_row = lds_a + (size_t)min(n, M - 1) * kr + 8 * g;
+    const bool a_real = n < M;
+    for (int qb = sr.q0; qb < sr.q1; qb += PFK) {
+#pragma unroll
+        for (int s = 0; s < PFK; ++s) {
+            const int q = qb + s;
+            bf16x8 af = {0, 0, 0, 0, 0, 0, 0, 0};
+            if (a_real && q < sr.q1) af = *(const bf16x8 *)(a_row + (q - sr.q0) * 32);
+#pragma unroll
+            for (int j = 0; j < NT; ++j)
+                acc[0][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, wbuf[s][j], acc[0][j], 0, 0, 0);
+#pragma unroll
+            for (int j = 0; j < NT; ++j) wbuf[s][j] = ld_w(j, q + PFK);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    if (tile0 >= n_tiles) return;
+    ChooseArgs none = {};
+    store_tiles<MT, NT>(acc, out, blockIdx.y, M, N, tile0, n_tiles, 0, lane, epi, none);
+}
+
 // ------------------------------------------------------------------ 32 < M: 32x32x16 MFMA, A through LDS
 // MTA: 32-row tiles per wave.  2 x 2 waves (WIDE false): the workgroup pass covers CTL = 2*MTA row tiles (9 when
 // MTA is 5: the second row half then repeats a tile whose results are dropped) of 128 columns.  WIDE: four waves
@@ -579,6 +802,19 @@ void launch_large(const bf16_t *a, const bf16_t *w, float *out, int M, int N, in
 }
 
 }  // namespace
+
+bool gemm_fuse_ok(int M, int N, int K) { return M >= 1 && M <= kFuseMaxRows && K <= kFuseMaxK && K % 32 == 0 && N % 16 == 0; }
+
+void launch_gemm_bf16_fused(const FuseArgs &f, const bf16_t *w, float *out, int M, int N, int K, const GemmPlan &p,
+                            int epi, hipStream_t st) {
+    dim3 grid((N + 127) / 128, p.splits, 1);
+    const int units = (K + SPLIT_UNIT - 1) / SPLIT_UNIT, per = (units + p.splits - 1) / p.splits;
+    const size_t smem = (size_t)M * per * SPLIT_UNIT * 2;             // bf16 rows of the largest share of K
+    if (f.kind == GEMM_FUSE_NORM)
+        gemm_bf16_small_fused_kernel<GEMM_FUSE_NORM><<<grid, 256, smem, st>>>(f, w, out, M, N, K, p.splits, epi);
+    else
+        gemm_bf16_small_fused_kernel<GEMM_FUSE_COMBINE><<<grid, 256, smem, st>>>(f, w, out, M, N, K, p.splits, epi);
+}
 
 GemmPlan plan_gemm_bf16(int M, int N, int K, bool force_single_split) {
     GemmPlan p;

@@ -194,6 +194,35 @@ void launch_gemm_bf16(const bf16_t *a, const bf16_t *w_packed, float *out, int M
                       int epi, hipStream_t st, const ChooseArgs *choose = nullptr);
 void launch_gemm_f32(const float *a, const float *w, float *out, int M, int N, int K, int out_row_major,
                      hipStream_t st);
+
+// The narrow GEMM (a handful of rows: the one-token step, very short blocks) with its producer folded in: instead
+// of reading a ready bf16 operand, every workgroup builds the rows it multiplies itself.
+//   GEMM_FUSE_NORM: A = rmsnorm(x_in + sum of the previous GEMM's split-K partial sums) * gain, rounded to bf16 (the
+//     whole residual row is summed by every workgroup, in the same order, for the row's mean square; workgroup
+//     (0, 0) also writes the updated residual stream to x_out, which must not be x_in);
+//   GEMM_FUSE_COMBINE: A = the attention output folded from the attention kernel's per-split partial results (only
+//     the heads of the workgroup's own share of K).
+// Saves one launch each (a dependent launch costs more than either prologue at these row counts).
+enum { GEMM_FUSE_NORM = 1, GEMM_FUSE_COMBINE = 2 };
+constexpr int kFuseMaxRows = 4;        // rows up to which the fused forms are used
+constexpr int kFuseMaxK = 4096;        // and the widest reduction they are built for
+struct FuseArgs {
+    int kind;
+    // GEMM_FUSE_NORM
+    const float *x_in;
+    float *x_out;
+    const float *part;         // tiled partial sums of the previous GEMM over the same rows, S copies
+    int S;
+    size_t split_stride;
+    const bf16_t *gain;
+    float eps;
+    // GEMM_FUSE_COMBINE: partial results as the attention kernel lays them out
+    const float *opart, *mpart, *lpart;
+    int R, n_q, n_kv, a_splits;
+};
+bool gemm_fuse_ok(int M, int N, int K);
+void launch_gemm_bf16_fused(const FuseArgs &f, const bf16_t *w_packed, float *out, int M, int N, int K,
+                            const GemmPlan &p, int epi, hipStream_t st);
 // plain row-major [M][K] -> A-fragment layout, and tiled partial sums -> plain row-major [M][N]
 void launch_pack_act(int dtype, const void *src, int M, int K, void *dst, hipStream_t st);
 void launch_untile_sum(const float *part, int S, int M, int N, float *out, hipStream_t st);

@@ -91,8 +91,8 @@ inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 inline size_t esize(int dtype) { return dtype == TIDAR_BF16 ? 2 : 4; }
 
 struct Layout {
-    size_t pos, rope_cs, x, xn, gemm_out, q, k_scr, v_scr, attn_part, o, h, xh, logits, logits_bytes, sel_logits, y,
-        total;
+    size_t pos, rope_cs, x, x2, xn, gemm_out, gemm_out2, q, k_scr, v_scr, attn_part, o, h, xh, logits, logits_bytes,
+        sel_logits, y, total;
     int attn_splits;
 };
 
@@ -131,6 +131,10 @@ Layout make_layout(const tidar_config &c, int B, int R, int n_mask, int Mh, int 
     l.pos = take((size_t)M * 4);
     l.rope_cs = take((size_t)M * c.head_dim * 4);
     l.x = take((size_t)M * c.d_model * 4);
+    // the fused chain of a few-row forward (see forward_rows) alternates between two residual buffers and two
+    // partial-sum areas: a GEMM that folds its producer in reads one pair while it writes the other
+    const bool fused_rows = c.dtype == TIDAR_BF16 && M <= kFuseMaxRows;
+    l.x2 = take(fused_rows ? (size_t)M * c.d_model * 4 : 0);
     l.xn = take(af_elems(M, c.d_model) * es);
     size_t g = gemm_out_floats(c, M, q_dim + 2 * kv_dim, c.d_model);
     size_t g2 = gemm_out_floats(c, M, c.d_model, q_dim);
@@ -140,6 +144,7 @@ Layout make_layout(const tidar_config &c, int B, int R, int n_mask, int Mh, int 
     g = g > g3 ? g : g3;
     g = g > g4 ? g : g4;
     l.gemm_out = take(g * 4);
+    l.gemm_out2 = take(fused_rows ? g * 4 : 0);
     l.q = take((size_t)M * q_dim * es);
     int n_mt = (n_mask + 15) / 16;
     l.k_scr = take((size_t)B * c.n_kv_heads * (n_mt > 0 ? n_mt : 1) * 16 * c.head_dim * es);
@@ -236,8 +241,10 @@ void gemm(tidar_ctx *ctx, const void *a, const void *w, float *out, int M, int N
     }
 }
 
-void attention(tidar_ctx *ctx, const Layout &l, char *ws, KvView kvv, const int32_t *prefix_len,
-               RowDesc d, int B, int max_keys, void *o_out, hipStream_t st) {
+// Returns the number of key splits whose partial results wait in the workspace (1: o_out holds the result).  With
+// defer_combine the partial results are left for the consumer to fold.
+int attention(tidar_ctx *ctx, const Layout &l, char *ws, KvView kvv, const int32_t *prefix_len,
+              RowDesc d, int B, int max_keys, void *o_out, hipStream_t st, bool defer_combine = false) {
     const tidar_config &c = ctx->cfg;
     if (c.dtype == TIDAR_BF16) {
         AttnPlan ap = plan_attention(B, c.n_kv_heads, c.n_q_heads / c.n_kv_heads, d.R, d.nc, max_keys);
@@ -247,16 +254,17 @@ void attention(tidar_ctx *ctx, const Layout &l, char *ws, KvView kvv, const int3
                                   (const bf16_t *)(ws + l.v_scr), prefix_len, d, B, c.n_q_heads, ap,
                                   (float *)(ws + l.attn_part), (bf16_t *)o_out, 1, st);
         }
-        if (ap.splits > 1) {
+        if (ap.splits > 1 && !defer_combine) {
             Prof p(ctx, KC_ATTN_COMBINE, st);
             launch_attention_combine((const float *)(ws + l.attn_part), B, d.R, c.n_q_heads, c.n_kv_heads, c.head_dim,
                                      ap.splits, (bf16_t *)o_out, 1, st);
         }
-    } else {
-        Prof p(ctx, KC_ATTN, st);
-        launch_attention_f32((const float *)(ws + l.q), kvv, (const float *)(ws + l.k_scr),
-                             (const float *)(ws + l.v_scr), prefix_len, d, B, c.n_q_heads, (float *)o_out, 1, st);
+        return ap.splits;
     }
+    Prof p(ctx, KC_ATTN, st);
+    launch_attention_f32((const float *)(ws + l.q), kvv, (const float *)(ws + l.k_scr),
+                         (const float *)(ws + l.v_scr), prefix_len, d, B, c.n_q_heads, (float *)o_out, 1, st);
+    return 1;
 }
 
 // What a scoring pass does with its logits instead of choosing tokens: rows cover text positions [c0, c0 + nc).
@@ -285,44 +293,104 @@ void forward_rows(tidar_ctx *ctx, const tidar_weights *w, const tidar_kv_cache *
                           (float *)(ws + l.rope_cs), st);
     }
     int S_prev = 0;   // split count of the partial sums still waiting to be added to the residual stream
+    // A forward of a few rows (the one-token step, very short blocks) is a chain of dependent launches whose kernels
+    // are much shorter than the hand-over between them: there the RMSNorms and the split-KV combine are folded into
+    // the GEMMs that consume them (5-6 launches per layer instead of 9).
+    const bool fuse = c.dtype == TIDAR_BF16 && gemm_fuse_ok(M, q_dim + 2 * kv_dim, c.d_model) &&
+                      gemm_fuse_ok(M, c.d_model, q_dim) && gemm_fuse_ok(M, 2 * c.d_ff, c.d_model);
+    float *x_alt = (float *)(ws + l.x2);
+    float *g_cur = gout, *g_alt = (float *)(ws + l.gemm_out2);      // g_cur: where the pending partial sums are
+    auto fused_norm_gemm = [&](const void *gain, const void *wmat, int N, float *dst, int epi, int *S_out) {
+        Prof p(ctx, KC_GEMM, st);
+        GemmPlan gp = plan_gemm_bf16(M, N, c.d_model, epi == GEMM_EPI_SWIGLU);
+        FuseArgs f = {};
+        f.kind = GEMM_FUSE_NORM;
+        f.x_in = x;
+        f.x_out = x_alt;
+        f.part = g_cur;
+        f.S = S_prev;
+        f.split_stride = pt_split_stride(M, c.d_model);
+        f.gain = (const bf16_t *)gain;
+        f.eps = c.rms_eps;
+        launch_gemm_bf16_fused(f, (const bf16_t *)wmat, dst, M, N, c.d_model, gp, epi, st);
+        *S_out = gp.splits;
+        float *t = x;          // the residual stream now lives in the other buffer
+        x = x_alt;
+        x_alt = t;
+    };
     for (int layer = 0; layer < c.n_layers; ++layer) {
         KvView kvv = layer_view(c, kv, layer);
-        {
-            Prof p(ctx, KC_RMSNORM, st);
-            launch_rmsnorm(c.dtype, x, gout, S_prev, w->attn_norm[layer], c.rms_eps, B, d.R, 0, c.d_model, ws + l.xn,
-                           st);
-        }
         int S = 1;
-        gemm(ctx, ws + l.xn, w->wqkv[layer], gout, M, q_dim + 2 * kv_dim, c.d_model, false, &S, st);
+        if (fuse) {
+            // reads (x, g_cur), writes the other residual buffer and the other partial-sum area
+            fused_norm_gemm(w->attn_norm[layer], w->wqkv[layer], q_dim + 2 * kv_dim, g_alt, GEMM_EPI_TILED, &S);
+            float *t = g_cur;
+            g_cur = g_alt;
+            g_alt = t;
+        } else {
+            {
+                Prof p(ctx, KC_RMSNORM, st);
+                launch_rmsnorm(c.dtype, x, g_cur, S_prev, w->attn_norm[layer], c.rms_eps, B, d.R, 0, c.d_model,
+                               ws + l.xn, st);
+            }
+            gemm(ctx, ws + l.xn, w->wqkv[layer], g_cur, M, q_dim + 2 * kv_dim, c.d_model, false, &S, st);
+        }
         {
             Prof p(ctx, KC_ROPE_KV, st);
-            launch_rope_kv(c.dtype, gout, S, (const float *)(ws + l.rope_cs), prefix_len, d, B, c.n_q_heads, kvv,
+            launch_rope_kv(c.dtype, g_cur, S, (const float *)(ws + l.rope_cs), prefix_len, d, B, c.n_q_heads, kvv,
                            ws + l.q, ws + l.k_scr, ws + l.v_scr, st);
         }
-        attention(ctx, l, ws, kvv, prefix_len, d, B, max_keys, ws + l.o, st);
-        gemm(ctx, ws + l.o, w->wo[layer], gout, M, c.d_model, q_dim, false, &S, st);
-        {
-            Prof p(ctx, KC_RMSNORM, st);
-            launch_rmsnorm(c.dtype, x, gout, S, w->ffn_norm[layer], c.rms_eps, B, d.R, 0, c.d_model, ws + l.xn, st);
+        const int a_splits = attention(ctx, l, ws, kvv, prefix_len, d, B, max_keys, ws + l.o, st, fuse);
+        if (fuse && a_splits > 1) {
+            Prof p(ctx, KC_GEMM, st);
+            GemmPlan gp = plan_gemm_bf16(M, c.d_model, q_dim, false);
+            const size_t rows = (size_t)B * c.n_kv_heads * a_splits * (c.n_q_heads / c.n_kv_heads) * d.R;
+            FuseArgs f = {};
+            f.kind = GEMM_FUSE_COMBINE;
+            f.opart = (const float *)(ws + l.attn_part);
+            f.mpart = f.opart + rows * c.head_dim;
+            f.lpart = f.mpart + rows;
+            f.R = d.R;
+            f.n_q = c.n_q_heads;
+            f.n_kv = c.n_kv_heads;
+            f.a_splits = a_splits;
+            launch_gemm_bf16_fused(f, (const bf16_t *)w->wo[layer], g_cur, M, c.d_model, q_dim, gp, GEMM_EPI_TILED, st);
+            S = gp.splits;
+        } else {
+            gemm(ctx, ws + l.o, w->wo[layer], g_cur, M, c.d_model, q_dim, false, &S, st);
         }
+        S_prev = S;
         bool fused_swiglu = false;
-        if (c.dtype == TIDAR_BF16) {
-            GemmPlan gp = plan_gemm_bf16(M, 2 * c.d_ff, c.d_model, false);
-            if (gp.splits == 1 && gp.m_chunks >= 1) {       // nothing to reduce: SwiGLU can live in the epilogue
-                Prof p(ctx, KC_GEMM, st);
-                launch_gemm_bf16((const bf16_t *)(ws + l.xn), (const bf16_t *)w->w_gate_up[layer],
-                                 (float *)(ws + l.h), M, 2 * c.d_ff, c.d_model, gp, GEMM_EPI_SWIGLU, st);
-                fused_swiglu = true;
+        if (fuse) {
+            // gate/up of a few rows always runs as one split, so SwiGLU lives in its epilogue
+            fused_norm_gemm(w->ffn_norm[layer], w->w_gate_up[layer], 2 * c.d_ff, (float *)(ws + l.h), GEMM_EPI_SWIGLU,
+                            &S);
+            fused_swiglu = true;
+        } else {
+            {
+                Prof p(ctx, KC_RMSNORM, st);
+                launch_rmsnorm(c.dtype, x, g_cur, S, w->ffn_norm[layer], c.rms_eps, B, d.R, 0, c.d_model, ws + l.xn,
+                               st);
+            }
+            if (c.dtype == TIDAR_BF16) {
+                GemmPlan gp = plan_gemm_bf16(M, 2 * c.d_ff, c.d_model, false);
+                if (gp.splits == 1 && gp.m_chunks >= 1) {       // nothing to reduce: SwiGLU can live in the epilogue
+                    Prof p(ctx, KC_GEMM, st);
+                    launch_gemm_bf16((const bf16_t *)(ws + l.xn), (const bf16_t *)w->w_gate_up[layer],
+                                     (float *)(ws + l.h), M, 2 * c.d_ff, c.d_model, gp, GEMM_EPI_SWIGLU, st);
+                    fused_swiglu = true;
+                }
             }
         }
         if (!fused_swiglu) {
-            gemm(ctx, ws + l.xn, w->w_gate_up[layer], gout, M, 2 * c.d_ff, c.d_model, false, &S, st);
+            gemm(ctx, ws + l.xn, w->w_gate_up[layer], g_cur, M, 2 * c.d_ff, c.d_model, false, &S, st);
             Prof p(ctx, KC_SWIGLU, st);
-            launch_swiglu(c.dtype, gout, S, M, c.d_ff, ws + l.h, st);
+            launch_swiglu(c.dtype, g_cur, S, M, c.d_ff, ws + l.h, st);
         }
-        gemm(ctx, ws + l.h, w->w_down[layer], gout, M, c.d_model, c.d_ff, false, &S, st);
+        gemm(ctx, ws + l.h, w->w_down[layer], g_cur, M, c.d_model, c.d_ff, false, &S, st);
         S_prev = S;
     }
+    gout = g_cur;
     if (head_row0 < 0) return;
     const int Rh = d.R - head_row0;
     const int Mh = B * Rh;
