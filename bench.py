@@ -5,16 +5,18 @@ A "step" is one pass of the whole hot path (row assembly .. next-draft select) o
 input: 8B-shaped model (36 layers, d 4096, 32 q / 8 kv heads, head_dim 128, ffn 12288, vocab 151936),
 bf16, batch 1, block length k = 16 (272 rows), prompt of 4096 random tokens already in the paged cache.
 
-Trained weights do not exist here, so random-init drafts are almost never accepted.  The timed steps
-therefore take their drafts from a reference continuation produced beforehand by the same step (greedy
-TiDAR decoding is token-identical to causal decoding), with each step's drafts correct up to a seeded
-acceptance length whose mean is the paper's tokens-per-forward for the 8B model (Table 2: 8.25) and wrong
-after it.  Verification, KV commit and draft selection all run for real in every timed step.
+The timed steps are the workload as named: random-init weights, the step's own next drafts fed back as the
+next step's drafts, greedy.  Trained weights do not exist here, so the drafts of an untrained diffusion head are
+almost never accepted: `value` is the measured decode rate at that natural acceptance (about one token per
+step); the hardware statement is `ms_per_step` and `tidar_over_ar_latency`, which do not depend on what is
+accepted.  Reported beside it under their own keys: the same step driven with drafts that are correct up to a
+seeded acceptance length whose mean is the paper's tokens-per-forward for the 8B model (Table 2: 8.25) -
+verification, KV commit and draft selection run for real, the drafts come from a reference continuation - and
+with fully correct drafts (upper bound, k tokens per step).
 
-Prints ONE JSON line (see the keys below).  Also reported: the 1-token AR step on the same state, the
-natural-acceptance and full-acceptance rates, the roofline of the dominant kernel (the weight-streaming
-skinny GEMM) from HIP events recorded by the library on the launch stream, and the CPU oracle timed on a
-bounded sample.
+Prints ONE JSON line (see the keys below).  Also reported: the 1-token AR step on the same state, the sampled
+(temperature 1) step, the roofline of the dominant kernel (the weight-streaming skinny GEMM) from HIP events
+recorded by the library on the launch stream, and the CPU oracle timed on one full-depth step.
 """
 import argparse
 import json
@@ -63,58 +65,70 @@ def parse():
     return ap.parse_args()
 
 
-def cpu_baseline(shape, k, L, mean_accept):
-    """Times the oracle as it stands on a bounded sample: TiDAR steps on 1- and 6-layer models of the benchmark's
-    shape (one untimed step to start the thread pool, then five timed ones each, about ten seconds of CPU work),
-    extrapolated linearly in the layer count to the full depth."""
+def cpu_baseline(shape, k, L):
+    """Times the oracle as it stands on ONE TiDAR step of the benchmark's workload at full depth (after one untimed
+    step that starts the thread pool and pages the weights in): the same seeded bf16 weights as the device run,
+    generated on the GPU and copied to the host, fp32 accumulation with the bf16 rounding points, a synthetic cache of
+    L tokens.  About ten seconds of CPU work at the 8B shape; tokens/s at the natural acceptance of that step."""
     import torch
     import tidar_inputs as TI
     from oracle import tidar_oracle as O
 
-    reps = 5
+    w = TI.make_weights(shape, seed=4, dtype=torch.bfloat16, device="cuda:0")
+    w_cpu = TI.weights_to(w, device="cpu")
+    del w
+    torch.cuda.empty_cache()
+    model = O.OracleModel(shape, w_cpu, dtype=torch.float32, bf16_faithful=True)
+    del w_cpu
+    st = model.new_state(L + 3 * k)
+    for l in range(shape.n_layers):
+        st.k[l][:L] = TI.make_normal((L, shape.n_kv_heads, shape.head_dim), 500 + l, torch.bfloat16).float()
+        st.v[l][:L] = TI.make_normal((L, shape.n_kv_heads, shape.head_dim), 600 + l, torch.bfloat16).float()
+    st.L = L
+    drafts = [int(t) for t in TI.make_drafts(shape, k, seed=9)[0]]
+    _, _, drafts, _ = model.tidar_step(st, drafts)
+    t0 = time.perf_counter()
+    a, _, drafts, _ = model.tidar_step(st, drafts)
+    dt = time.perf_counter() - t0
+    return {"value": a / dt, "unit": "tokens/s", "cores": torch.get_num_threads(), "kind": "oracle",
+            "sample": f"one oracle TiDAR step of the full {shape.n_layers}-layer {shape.name} model (k={k}, prefix {L}, "
+                      f"fp32 accumulation, bf16 rounding points) after one untimed step: {dt:.2f} s, {a} token(s) "
+                      f"accepted (random-init weights)",
+            "step_s": dt}
 
-    def one(n_layers):
-        sh = shape.with_layers(n_layers)
-        w = TI.make_weights(sh, seed=4, dtype=torch.bfloat16)
-        model = O.OracleModel(sh, w, dtype=torch.float32, bf16_faithful=True)
-        st = model.new_state(L + (reps + 2) * k)
-        for l in range(n_layers):
-            st.k[l][:L] = TI.make_normal((L, sh.n_kv_heads, sh.head_dim), 500 + l, torch.bfloat16).float()
-            st.v[l][:L] = TI.make_normal((L, sh.n_kv_heads, sh.head_dim), 600 + l, torch.bfloat16).float()
-        st.L = L
-        drafts = [int(t) for t in TI.make_drafts(sh, k, seed=9)[0]]
-        _, _, drafts, _ = model.tidar_step(st, drafts)
-        t0 = time.perf_counter()
-        for _ in range(reps):
-            _, _, drafts, _ = model.tidar_step(st, drafts)
-        return (time.perf_counter() - t0) / reps
 
-    n_hi = min(6, shape.n_layers)
-    t1, t2 = one(1), one(n_hi)
-    per_layer = max((t2 - t1) / max(n_hi - 1, 1), 1e-9)
-    head = max(t1 - per_layer, 0.0)
-    full = head + per_layer * shape.n_layers
-    return {"value": mean_accept / full, "unit": "tokens/s", "cores": torch.get_num_threads(), "kind": "oracle",
-            "sample": f"{reps} oracle TiDAR steps each (k={k}, prefix {L}, fp32 accumulation, bf16 rounding points) on 1- "
-                      f"and {n_hi}-layer {shape.name} models ({t1:.2f} s, {t2:.2f} s per step), extrapolated linearly to "
-                      f"{shape.n_layers} layers = {full:.1f} s/step, at {mean_accept} tokens/step",
-            "step_s": full}
+def gemm_source_digest():
+    """Digest of the sources the GEMM launches are built from: a traffic summary measured on another build does not
+    describe this one."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in ("kernels_gemm.hip", "tidar_internal.h"):
+        with open(os.path.join(ROOT, "paper_2511_08923_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
 
 
 def read_traffic_summary(shape_name, k, prefix):
     """HBM bytes per GEMM launch measured with rocprofv3 --pmc (FETCH_SIZE and WRITE_SIZE runs, scaled by a copy of
     known size): counters cannot be collected from inside this process, so the figure comes from the committed
-    summary of those runs for this workload (line 'traffic_bytes_per_launch: N'), or is null when there is none."""
-    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles",
-                        f"gemm_traffic_{shape_name}_k{k}_prefix{prefix}_pmc.md")
+    summary of those runs for this workload (lines 'traffic_bytes_per_launch: N' and 'gemm_source_digest: H').  It is
+    null when there is no summary or when the summary was measured on other GEMM sources than the ones built here."""
+    rel = os.path.join("profiles", f"gemm_traffic_{shape_name}_k{k}_prefix{prefix}_pmc.md")
+    traffic, digest = None, None
     try:
-        with open(path) as f:
+        with open(os.path.join(ROOT, rel)) as f:
             for line in f:
                 if line.startswith("traffic_bytes_per_launch:"):
-                    return float(line.split(":")[1]), os.path.relpath(path, os.path.dirname(os.path.abspath(__file__)))
+                    traffic = float(line.split(":")[1])
+                if line.startswith("gemm_source_digest:"):
+                    digest = line.split(":")[1].strip()
     except OSError:
-        pass
-    return None, None
+        return None, "no committed pmc summary for this workload"
+    if traffic is None:
+        return None, f"{rel} holds no traffic_bytes_per_launch line"
+    if digest != gemm_source_digest():
+        return None, f"{rel} was measured on other GEMM sources (digest {digest}, built {gemm_source_digest()}): stale"
+    return traffic, rel
 
 
 def attention_microbench(args, torch, T, TI, dev):
@@ -344,6 +358,7 @@ def main():
 
     # ---- untimed set-up: prefill, then the reference continuation by natural TiDAR steps (also a warm-up)
     drafts, _ = eng.prefill(prompt, k, mode)
+    first_drafts = drafts.clone()
     out = (torch.empty(1, dtype=torch.int32, device=dev), torch.empty(1, k, dtype=torch.int32, device=dev),
            torch.empty(1, k, dtype=torch.int32, device=dev))
     stream = torch.zeros(ref_tokens + 2 * k, dtype=torch.int32, device=dev)
@@ -374,6 +389,10 @@ def main():
     one = torch.ones(1, dtype=torch.int64, device=dev)
 
     def one_step(full):
+        if full == "natural":                               # the step's own next drafts, as a decode loop feeds them
+            drafts_buf.copy_(out[2])
+            eng.step(drafts_buf, k, hint=hint_all, mode=step_mode[0], out=out)
+            return
         base = eng.prefix_len[:1].long() - P
         tok = stream[base + ar]
         if full:
@@ -419,9 +438,28 @@ def main():
             if count is not None:
                 count[i] = out[0][0]
 
-    # ---- timed: TiDAR steps at the paper's acceptance mix
+    # ---- timed: the workload as named (random-init weights, the step's own drafts fed back, greedy)
+    step_mode = [mode]
     stepper(False)
     stepper(True)
+    stepper("natural")
+
+    def natural_run(n_warm, n):
+        reset()
+        out[2].copy_(first_drafts)
+        run_steps(n_warm, 0, full="natural")
+        c = torch.zeros(n, dtype=torch.int32, device=dev)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run_steps(n, n_warm, full="natural", count=c)
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0, int(c.sum())
+
+    t_tidar, tokens = natural_run(args.warmup, args.steps)
+    step_ms = t_tidar / args.steps * 1e3
+
+    # ---- the same step at the paper's acceptance mix: drafts from the reference continuation, correct up to a
+    # seeded length (a projection of what trained weights would accept, with real verification)
     reset()
     run_steps(args.warmup, 0)
     counts = torch.zeros(args.steps, dtype=torch.int32, device=dev)
@@ -429,10 +467,19 @@ def main():
     t0 = time.perf_counter()
     run_steps(args.steps, args.warmup, count=counts)
     torch.cuda.synchronize()
-    t_tidar = time.perf_counter() - t0
-    tokens = int(counts.sum())
-    step_ms = t_tidar / args.steps * 1e3
+    t_forced = time.perf_counter() - t0
+    tokens_forced = int(counts.sum())
     forced_ok = bool((counts == acc_len[args.warmup:args.warmup + args.steps]).all())
+
+    # ---- the sampled step (temperature 1, seeded): the Gumbel noise is added in the LM head's epilogue
+    if not args.no_graph:
+        graphs.pop("natural")
+    step_mode[0] = T.make_mode(sample=True, temperature=1.0, seed=2024)
+    t_sampled, _ = natural_run(min(args.warmup, 3), min(args.steps, 20))
+    sampled_step_ms = t_sampled / min(args.steps, 20) * 1e3
+    step_mode[0] = mode
+    if not args.no_graph:
+        graphs.pop("natural")
 
     # ---- per-step latency spread: the same steps once more, an event pair around each replay (kept out of the
     # timed region above so that the headline number has no events inside it)
@@ -549,21 +596,34 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "launch": "host launches" if args.no_graph else "HIP graph replay of the captured step",
         "config": {"workload": f"{shape.name} TiDAR decode, batch 1, k={k} ({R} rows/step), prompt {P} random tokens, "
-                               f"greedy, acceptance lengths seeded with mean {args.mean_accept} (paper Table 2)",
+                               f"random-init weights, greedy, the step's own drafts fed back (natural acceptance)",
                    "k": k, "prefix_len": P, "batch": 1, "layers": shape.n_layers},
-        "tidar_step_ms": step_ms, "tidar_step_ms_percentiles": step_pcts, "ar_step_ms": ar_ms, "tidar_over_ar_latency": step_ms / ar_ms,
+        "value_note": "tokens/s at the natural acceptance of random-init weights (about one token per step: an "
+                      "untrained diffusion head drafts nothing the causal logits accept); the step latency does not "
+                      "depend on acceptance, see paper_acceptance_projection for the same step at the paper's mix",
+        "tidar_step_ms": step_ms, "tidar_step_ms_percentiles": step_pcts, "ar_step_ms": ar_ms,
+        "tidar_over_ar_latency": step_ms / ar_ms, "tidar_over_ar_latency_target": 1.3,
         "ar_tokens_per_s": 1e3 / ar_ms, "tokens_per_step": tokens / args.steps,
-        "speedup_vs_ar_tokens_per_s": (tokens / t_tidar) / (1e3 / ar_ms),
-        "forced_acceptance_reproduced": forced_ok,
-        "natural_acceptance_tokens_per_s": natural_tok_s, "natural_tokens_per_step": n_ref / nat_steps,
+        "sampled_step_ms": sampled_step_ms, "sampled_over_greedy_step": sampled_step_ms / step_ms,
+        "paper_acceptance_projection": {
+            "what": f"the same step fed drafts from a reference continuation that are correct up to a seeded length "
+                    f"(mean {args.mean_accept} = the paper's Table 2 tokens per forward, trained 8B model); verification, "
+                    f"commit and draft selection run for real",
+            "tokens_per_s": tokens_forced / t_forced, "tokens_per_step": tokens_forced / args.steps,
+            "ms_per_step": t_forced / args.steps * 1e3, "forced_acceptance_reproduced": forced_ok,
+            "speedup_vs_ar_tokens_per_s": (tokens_forced / t_forced) / (1e3 / ar_ms)},
         "full_acceptance_tokens_per_s": full_tok_s,
         "step_hbm_GBs": (wbytes + kv_bytes) / (step_ms * 1e-3) / 1e9,
         "ar_step_hbm_GBs": (wbytes + kv_bytes) / (ar_ms * 1e-3) / 1e9,
-        "ar_step_hbm_frac": (wbytes + kv_bytes) / (ar_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "ar_step_hbm_frac": (wbytes + kv_bytes) / (ar_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "ar_step_hbm_frac_target": 0.70,
         "roofline": roofline,
         "ar_gemm_GBs": wbytes / (ar_gemm["ms"] / n_prof * 1e-3) / 1e9,
         "kernel_ms_per_tidar_step": {n: v["ms"] / n_prof for n, v in prof_tidar.items()},
         "kernel_ms_per_ar_step": {n: v["ms"] / n_prof for n, v in prof_ar.items()},
+        "parity_note": "logit tolerance: 2e-2 absolute holds on the small test models; at the full 28/36-layer depth "
+                       "with N(0, 0.02) weights no bf16 implementation can hold it (the oracle with fp32 accumulation is "
+                       "0.15 max / 0.024 rms away from the same oracle with fp64 accumulation at the 8B shape): the "
+                       "full-depth tests allow 1.5x that measured floor and compare tokens under a near-tie rule",
         "paper_context": "paper reports 5.91x tokens/s over AR for its 8B model on one H100 (Figure 4); other "
                          "hardware, trained weights: context only",
     }
@@ -571,7 +631,7 @@ def main():
     del eng
     torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
-        res["cpu_baseline"] = cpu_baseline(TI.SHAPES[args.shape], k, P, args.mean_accept)
+        res["cpu_baseline"] = cpu_baseline(shape, k, P)
     else:
         res["cpu_baseline"] = None
     print(json.dumps(res))
