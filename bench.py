@@ -53,6 +53,8 @@ def parse():
                          "(one JSON line per point on stdout)")
     ap.add_argument("--sweep-batches", type=str, default="1,4,8,16,32")
     ap.add_argument("--sweep-ks", type=str, default="4,8,16")
+    ap.add_argument("--sweep-tokens", type=int, default=256,
+                    help="tokens every sequence of a sweep point generates (natural acceptance: one step per token)")
     ap.add_argument("--score-bench", action="store_true",
                     help="time the many-row entry points on a --prefix-token text: tidar_prefill, tidar_score with the "
                          "causal section only (AR-mode likelihood) and with the mask section (training layout, block "
@@ -217,15 +219,19 @@ def score_bench(args, shape, torch, T, TI, dev):
 
 
 def sweep(args, shape, torch, T, TI, dev):
-    """TiDAR-step vs AR-step latency over batch and block length (the free-slot regime and its crossover).
-    The cache is filled synthetically (N(0,1) K/V, as in the attention micro-benchmark): step latency does not
-    depend on token values, and a real prefill of batch x prefix tokens would only lengthen the set-up."""
+    """TiDAR-step vs AR-step latency over batch and block length (the free-slot regime and its crossover): every
+    point generates --sweep-tokens tokens per sequence from a context of --prefix tokens, the step's own drafts fed
+    back (random-init weights accept about one token per step, so that is one step per token; the prefix grows as
+    it would in a decode loop), and the 1-token AR step generates as many.  The cache is filled synthetically
+    (N(0,1) K/V, as in the attention micro-benchmark): step latency does not depend on token values, and a real
+    prefill of batch x prefix tokens would only lengthen the set-up."""
     batches = [int(x) for x in args.sweep_batches.split(",")]
     ks = [int(x) for x in args.sweep_ks.split(",")]
-    P = args.prefix
+    P, n_tok = args.prefix, args.sweep_tokens
     bmax, kmax = max(batches), max(ks)
     w = TI.make_weights(shape, seed=4, dtype=torch.bfloat16, device=dev)
-    eng = T.Engine(shape, w, dtype=T.TIDAR_BF16, max_k=kmax, max_batch=bmax, max_seq_len=P + 64 * kmax, device=dev,
+    max_seq = P + n_tok * kmax + 4 * kmax                   # every step could accept k tokens
+    eng = T.Engine(shape, w, dtype=T.TIDAR_BF16, max_k=kmax, max_batch=bmax, max_seq_len=max_seq, device=dev,
                    free_source=True)
     del w
     torch.cuda.empty_cache()
@@ -237,16 +243,6 @@ def sweep(args, shape, torch, T, TI, dev):
     mode = T.make_mode()
     wbytes = eng.weight_bytes_per_step()
     kv_per_tok = 2 * shape.n_layers * shape.n_kv_heads * shape.head_dim * 2
-
-    def timed(fn, n_warm, n):
-        for _ in range(n_warm):
-            fn()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(n):
-            fn()
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t0) / n * 1e3
 
     def graphed(body):
         if args.no_graph:
@@ -261,36 +257,69 @@ def sweep(args, shape, torch, T, TI, dev):
             body()
         return gr.replay
 
-    rows = []
+    def generate(fn, B, reset):
+        """n_tok steps from the reset state (a step accepts at least one token per sequence); ms per step and the
+        tokens the sequences really advanced by."""
+        reset()
+        for _ in range(min(args.warmup, 5)):
+            fn()
+        reset()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n_tok):
+            fn()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        return dt / n_tok * 1e3, int((eng.prefix_len[:B] - P).sum()), dt
+
     for B in batches:
-        tok_in = TI.make_drafts(shape, 1, seed=11, batch=B).to(dev).view(B).contiguous()
+        tok0 = TI.make_drafts(shape, 1, seed=11, batch=B).to(dev).view(B).contiguous()
+        tok_buf = tok0.clone()
         tok_out = torch.empty(B, dtype=torch.int32, device=dev)
 
         def ar_body():
-            eng.prefix_len[:B].fill_(P)                   # keep the prefix length fixed across timed steps
-            eng.ar_step(tok_in, hint=P, mode=mode, out=tok_out)
+            eng.ar_step(tok_buf, hint=P + n_tok, mode=mode, out=tok_out)
+            tok_buf.copy_(tok_out)
 
-        ar_ms = timed(graphed(ar_body), args.warmup, args.steps)
+        def ar_reset():
+            eng.prefix_len[:B].fill_(P)
+            tok_buf.copy_(tok0)
+
+        ar_ms, ar_tokens, ar_dt = generate(graphed(ar_body), B, ar_reset)
         for k in ks:
             R = k * (k + 1)
-            drafts = TI.make_drafts(shape, k, seed=12, batch=B).to(dev)
+            d0 = TI.make_drafts(shape, k, seed=12, batch=B).to(dev)
+            drafts = d0.clone()
             out = (torch.empty(B, dtype=torch.int32, device=dev), torch.empty(B, k, dtype=torch.int32, device=dev),
                    torch.empty(B, k, dtype=torch.int32, device=dev))
 
-            def td_body():
-                eng.prefix_len[:B].fill_(P)
-                eng.step(drafts, k, hint=P, mode=mode, out=out)
+            # bound on the prefix length for the whole run (the library cuts its attention splits from it): random-init
+            # weights accept about one token per step; the bound is checked after the run
+            bound = P + 2 * n_tok + k
 
-            td_ms = timed(graphed(td_body), args.warmup, args.steps)
-            flops = 2.0 * B * R * (wbytes / 2) + 4.0 * shape.n_layers * shape.n_q_heads * B * R * P * shape.head_dim
-            row = {"sweep": True, "batch": B, "k": k, "rows": B * R, "prefix_len": P, "tidar_step_ms": td_ms,
+            def td_body():
+                eng.step(drafts, k, hint=bound, mode=mode, out=out)
+                drafts.copy_(out[2])
+
+            def td_reset():
+                eng.prefix_len[:B].fill_(P)
+                drafts.copy_(d0)
+
+            td_ms, td_tokens, td_dt = generate(graphed(td_body), B, td_reset)
+            if int(eng.prefix_len[:B].max()) > bound:
+                raise RuntimeError("a sequence outgrew the length bound given to tidar_step")
+            L_mid = P + n_tok // 2
+            flops = 2.0 * B * R * (wbytes / 2) + 4.0 * shape.n_layers * shape.n_q_heads * B * R * L_mid * shape.head_dim
+            row = {"sweep": True, "batch": B, "k": k, "rows": B * R, "prefix_len": P, "steps": n_tok,
+                   "tokens_generated_per_sequence": td_tokens / B, "tidar_step_ms": td_ms,
                    "ar_step_ms": ar_ms, "tidar_over_ar_latency": td_ms / ar_ms,
-                   "tidar_step_hbm_GBs": (wbytes + B * kv_per_tok * P) / (td_ms * 1e-3) / 1e9,
-                   "ar_step_hbm_GBs": (wbytes + B * kv_per_tok * P) / (ar_ms * 1e-3) / 1e9,
+                   "tidar_tokens_per_s_natural": td_tokens / td_dt, "ar_tokens_per_s": ar_tokens / ar_dt,
+                   "tidar_step_hbm_GBs": (wbytes + B * kv_per_tok * L_mid) / (td_ms * 1e-3) / 1e9,
+                   "ar_step_hbm_GBs": (wbytes + B * kv_per_tok * L_mid) / (ar_ms * 1e-3) / 1e9,
+                   "ar_step_hbm_frac": (wbytes + B * kv_per_tok * L_mid) / (ar_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                    "tidar_step_tflops": flops / (td_ms * 1e-3) / 1e12,
                    "tidar_step_mfma_frac": flops / (td_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
                    "layers": shape.n_layers, "shape": shape.name}
-            rows.append(row)
             print(json.dumps(row), flush=True)
     eng.close()
 
