@@ -185,7 +185,8 @@ tidar_status tidar_prefill(tidar_ctx *ctx, const tidar_weights *w, const tidar_k
  *   logits_out  optional dev fp32 [batch][k(k+1)][vocab], rows in the order
  *               c_0..c_{k-1}, blk_0[0..k), ..., blk_{k-1}[0..k)
  *   max_prefix_len_hint  host upper bound of every prefix_len[b] on entry (capacity check, grid sizing).
- *               The attention kernel cuts the key range into equal splits of this bound, so a key's split depends
+ *               The attention kernel cuts the key range into equal splits of this bound (rounded up to a multiple
+ *               of 256 keys, so that nearby bounds cut alike), so a key's split depends
  *               on its position and the bound, not on the current length: with one bound held over a run of calls
  *               (e.g. the length the generation may reach) a row with the same context gets bit-identical logits
  *               at every step; a bound far above the real length leaves the later splits empty (slower, still

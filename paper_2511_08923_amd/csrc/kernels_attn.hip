@@ -187,14 +187,17 @@ __device__ inline bool attn_block_fixed_ref(const bf16_t *k_lds, const bf16_t *v
     // K as A operand: lane = (tile row, hd half of the k step); V^T as A operand: lane = (d, key half of the unit)
     auto k_frag = [&](int ks) { return *(const bf16x8 *)(kb + lq * 256 + (((2 * ks + lh) ^ (lq & 15)) << 4)); };
     auto v_frag = [&](int dt, int u) { return *(const bf16x8 *)(vb + (((u * 2 + lh) * 128 + 32 * dt + lq) << 4)); };
+    // all eight K fragments are asked for before the first MFMA: read one or two ahead of its MFMA, as the compiler
+    // orders them by itself, every link of the score chain waits out a full LDS round trip
+    bf16x8 kf[8];
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) kf[ks] = k_frag(ks);
+    __builtin_amdgcn_sched_barrier(0);
     f32x16 s;
 #pragma unroll
     for (int e = 0; e < 16; ++e) s[e] = 0.f;
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-        const bf16x8 kf0 = k_frag(ks);
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf0, qf[ks], s, 0, 0, 0);
-    }
+    for (int ks = 0; ks < 8; ++ks) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[ks], s, 0, 0, 0);
     bf16x8 vf[2][2];
 #pragma unroll
     for (int dt = 0; dt < 2; ++dt)
@@ -688,6 +691,9 @@ AttnPlan plan_attention(int B, int n_kv, int group, int R, int nc, int max_keys)
     p.tiles_per_chunk = TQ < 4 ? TQ : 4;      // four waves x one query tile each
     p.n_chunks = (TQ + p.tiles_per_chunk - 1) / p.tiles_per_chunk;
     int base = B * n_kv * p.n_chunks;
+    // the caller's bound is taken in steps of 256 keys: bounds that differ by less cut the keys alike, so results do
+    // not change bit for bit because a caller's estimate of the final length moved a little
+    max_keys = (max_keys + 255) & ~255;
     int iters = (max_keys + 31) / 32;
     // Two workgroups are resident per CU (512 slots).  A split costs about eight key-pair iterations of prologue
     // and partial-sum epilogue; a grid of w slot-fulls takes about w + 1/2 workgroup times (the last round is

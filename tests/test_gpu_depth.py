@@ -256,3 +256,44 @@ def test_8b_full_depth_tidar_stream_equals_one_token_stream_on_device_greedy(T, 
 def test_8b_full_depth_tidar_stream_equals_one_token_stream_on_device_sampled(T, m8, progress):
     device_stream_check(T, m8.eng, m8.shape, 4096, 1024, T.make_mode(sample=True, temperature=1.0, seed=321),
                         O.Mode(sample=True, temperature=1.0, seed=321), 0.12, progress, "8b-shape/36L T=1")
+
+
+def test_8b_full_depth_two_sequences_of_8192_tokens_vs_oracle(T, progress):
+    """The sweep's shape at full depth (config 5: 8192-token contexts, several sequences per step): two sequences
+    with caches of 8192 and 8000 tokens, k = 16, i.e. 544 rows per step - the many-row GEMM class (256 x 256
+    workgroup tiles, three row passes) and a batched attention launch at the real model dimensions - against the
+    fp32 oracle run for each sequence alone.  Tolerance: the 36-layer floor of this file's header."""
+    sh = TI.SHAPE_8B
+    lens = [8192, 8000]
+    w = TI.make_weights(sh, seed=4, dtype=torch.bfloat16, device="cuda")
+    w_cpu = TI.weights_to(w, device="cpu")
+    eng = T.Engine(sh, w, dtype=T.TIDAR_BF16, max_k=K, max_batch=2, max_seq_len=8192 + 4 * K, free_source=True)
+    del w
+    torch.cuda.empty_cache()
+    model = O.OracleModel(sh, w_cpu, dtype=torch.float32, bf16_faithful=True)
+    del w_cpu
+    progress("  8b-shape/36L x2: fp32 oracle built")
+    drafts = [[int(t) for t in TI.make_drafts(sh, K, seed=19 + b)[0]] for b in range(2)]
+    want = []
+    for b, L in enumerate(lens):
+        st = model.new_state(L + 2 * K, seq_id=b)
+        for l in range(sh.n_layers):
+            st.k[l][:L] = TI.make_normal((L, sh.n_kv_heads, sh.head_dim), 700 + 40 * b + l, torch.bfloat16).float()
+            st.v[l][:L] = TI.make_normal((L, sh.n_kv_heads, sh.head_dim), 800 + 40 * b + l, torch.bfloat16).float()
+        st.L = L
+        load_oracle_state_into_engine(eng, st, seq=b)
+        want.append(model.tidar_step(st, drafts[b]) + (st.L,))
+        progress(f"  8b-shape/36L x2: oracle step of sequence {b} done (a = {want[-1][0]})")
+        del st
+    a, acc, nxt, lg = eng.step(torch.tensor(drafts, dtype=torch.int32, device="cuda"), K, hint=max(lens),
+                               want_logits=True)
+    torch.cuda.synchronize()
+    par = StepParity("8b-shape 36 layers, 2 sequences")
+    for b in range(2):
+        a_o, acc_o, nxt_o, lg_o, L_new = want[b]
+        got = (int(a[b]), acc[b].tolist(), nxt[b].tolist(), int(eng.prefix_len[b]))
+        err, rms, rows = par.check(K, lg[b].cpu(), got, lg_o.double(), (a_o, acc_o, nxt_o, L_new), 1.5 * 0.15,
+                                   rms_tol=1.5 * 0.024)
+        progress(f"  8b-shape/36L x2 sequence {b}: max err {err:.3e} rms {rms:.3e} near-tie rows {len(rows)}")
+    par.report(min_exact=0)
+    eng.close()
