@@ -495,7 +495,7 @@ __global__ __launch_bounds__(256) void score_loss_kernel(const float *__restrict
 
 // ------------------------------------------------------------------ verify / accept / commit / next-draft select
 // y: [B][k(k+1)] chosen token per row (rows: c_0..c_{k-1}, blk_0[0..k), ...).  One wavefront per sequence: lane i
-// holds draft i, the token its causal row chose and the verdict "draft i is what row i-1 chose"; the acceptance
+// holds draft i, the token its causal row chose and the answer to "is draft i what row i-1 chose"; the acceptance
 // length is the position of the first lane that says no.  The same wavefront is the call's device-side checker:
 // a sequence that did not fit the page table, that wrote through a page id outside the pool, that was fed a token
 // id outside the vocabulary or whose needed rows chose no token (all NaN) is reported with accepted_len 0, its
