@@ -542,9 +542,12 @@ def main():
 
     tin_buf = torch.zeros(1, dtype=torch.int32, device=dev)
 
+    tin_buf.copy_(stream[:1])
+
     def one_ar():
-        tin_buf.copy_(stream[eng.prefix_len[:1].long() - P])
+        # ordinary one-token decoding: each step's token is the next step's input (one copy, no host work)
         eng.ar_step(tin_buf, hint=hint_all, mode=mode, out=tok_out)
+        tin_buf.copy_(tok_out)
 
     if args.no_graph:
         ar_fn = one_ar
