@@ -179,6 +179,7 @@ __device__ inline void attn_block(const bf16_t *k_lds, const bf16_t *v_lds, int 
 // rule).  bf16 rounding is a matter of the mantissa alone, and every quantity (numerators, denominator, O^T)
 // carries the same power of two.  No rescale arm means no branch that rejoins around the accumulators: with one,
 // the compiler copied all 64 accumulator registers twice per block.
+template <bool PRIO>
 __device__ inline bool attn_block_fixed_ref(const bf16_t *k_lds, const bf16_t *v_lds, int lq, int lh,
                                             const bf16x8 (&qf)[8], f32x16 (&acc)[4], float m_run, float &l_run,
                                             float c) {
@@ -198,10 +199,12 @@ __device__ inline bool attn_block_fixed_ref(const bf16_t *k_lds, const bf16_t *v
     for (int e = 0; e < 16; ++e) s[e] = 0.f;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[ks], s, 0, 0, 0);
-    // The softmax section runs at a raised wave priority: the SIMD's other wave is then the one that waits while it
-    // is in an MFMA chain of its own, and the two fall into opposite phases more often (measured: -3 %; raising the
-    // priority of the MFMA chains instead changes nothing).
-    __builtin_amdgcn_s_setprio(3);
+    // PRIO (launches in which all four waves hold a query tile): the softmax section runs at a raised wave priority.
+    // The SIMD's other wave is then the one that waits while it is in an MFMA chain of its own, and the two fall into
+    // opposite phases more often (measured: -3 % at 272 rows, -1 % at batch 8; raising the priority of the MFMA
+    // chains instead changes nothing).  Not for the few-row shapes, whose three other waves only move tiles: there
+    // the raised wave holds up their loads (1-token step at batch 8: +2.6 %).
+    if (PRIO) __builtin_amdgcn_s_setprio(3);
     bf16x8 vf[2][2];
 #pragma unroll
     for (int dt = 0; dt < 2; ++dt)
@@ -211,7 +214,7 @@ __device__ inline bool attn_block_fixed_ref(const bf16_t *k_lds, const bf16_t *v
 #pragma unroll
     for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[e]);
     if (__any(!(mx * c <= m_run + 60.f))) {                       // also refuses a reference that is still -inf
-        __builtin_amdgcn_s_setprio(0);
+        if (PRIO) __builtin_amdgcn_s_setprio(0);
         return false;
     }
     const bf16x2 ones = {(bf16_t)1.0f, (bf16_t)1.0f};
@@ -226,7 +229,7 @@ __device__ inline bool attn_block_fixed_ref(const bf16_t *k_lds, const bf16_t *v
         pf[e >> 3][(e & 7) + 1] = pk[1];
     }
     l_run += psum;
-    __builtin_amdgcn_s_setprio(0);
+    if (PRIO) __builtin_amdgcn_s_setprio(0);
     bf16x8 vg[2][2];
 #pragma unroll
     for (int dt = 0; dt < 2; ++dt)
@@ -246,7 +249,7 @@ __device__ inline bool attn_block_fixed_ref(const bf16_t *k_lds, const bf16_t *v
 }
 
 // QT: 32-row query tiles per wave.
-template <int QT>
+template <int QT, bool PRIO>
 __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
     constexpr int NBUF = 3, K_TILE = TILE, V_TILE = TILE;
     __shared__ __attribute__((aligned(16))) bf16_t k_lds[NBUF][K_TILE];
@@ -553,7 +556,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
                 for (int i = 0; i < QT; ++i) {
                     const int tile = t0 + wave + 4 * i;
                     if (tile < t1)
-                        ok = ok && attn_block_fixed_ref(k_lds[b_cur], v_lds[b_cur], lq, lh, qf[i], acc[i], m_run[i],
+                        ok = ok && attn_block_fixed_ref<PRIO>(k_lds[b_cur], v_lds[b_cur], lq, lh, qf[i], acc[i], m_run[i],
                                                              l_run[i], a.scale_log2e);
                 }
                 if (!ok) break;
@@ -766,7 +769,8 @@ void launch_attention_bf16(const bf16_t *q, KvView kv, const bf16_t *k_scr, cons
     a.xcd_q = a.n_groups % 8 == 0 ? 1 : (a.n_groups < 8 && 8 % a.n_groups == 0) ? 8 / a.n_groups : 0;
     dim3 grid(a.n_groups * p.n_chunks, p.splits);
     if (a.xcd_q > 1) grid.x = 8 * ((p.n_chunks + a.xcd_q - 1) / a.xcd_q);
-    attn_bf16_kernel<1><<<grid, 256, 0, st>>>(a);
+    if (p.tiles_per_chunk == 4) attn_bf16_kernel<1, true><<<grid, 256, 0, st>>>(a);
+    else attn_bf16_kernel<1, false><<<grid, 256, 0, st>>>(a);
 }
 
 void launch_attention_combine(const float *part, int B, int R, int n_q, int n_kv, int hd, int splits, bf16_t *out,
