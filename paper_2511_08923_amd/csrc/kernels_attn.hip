@@ -77,6 +77,7 @@ struct AttnArgs {
     bf16_t *out;               // single split only: [rows][n_q][HD], or the A-fragment layout (out_af)
     int out_af;
     ActLayout lay;
+    AttnRope rp;               // ROPE kernels only
 };
 
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
@@ -249,11 +250,12 @@ __device__ inline bool attn_block_fixed_ref(const bf16_t *k_lds, const bf16_t *v
 }
 
 // QT: 32-row query tiles per wave.
-template <int QT, bool PRIO>
+template <int QT, bool PRIO, bool ROPE>
 __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
     constexpr int NBUF = 3, K_TILE = TILE, V_TILE = TILE;
     __shared__ __attribute__((aligned(16))) bf16_t k_lds[NBUF][K_TILE];
     __shared__ __attribute__((aligned(16))) bf16_t v_lds[NBUF][V_TILE];
+    __shared__ __attribute__((aligned(16))) bf16_t q_lds[ROPE ? 32 * HD : 8];     // ROPE: the rotated Q rows of the group
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // known to be uniform: scalar registers
@@ -332,6 +334,90 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
     const int nA = a1 - a0, n_seq = nA + (b1 - b0);
     auto seq_it = [&](int n) { return n < nA ? a0 + n : b0 + (n - nA); };
 
+    if constexpr (ROPE) {
+        // One row per sequence (R = 1): the group's query heads are the tile's rows.  A thread takes one rotation pair
+        // (d, d + 64) of one head: it adds the split-K partial sums of the QKV projection and rotates by the row's
+        // angles, exactly as the RoPE kernel does.  The workgroup whose key range holds the new row's position does
+        // the same for K and copies V, and stores both into the cache page before any of its tile loads starts
+        // (the stores are waited for, then a workgroup barrier: the loads that follow read them back from L2).
+        const AttnRope &rp = a.rp;
+        const int row = b;                                   // the call's row of this sequence
+        const float *cs = rp.rope_cs + (size_t)row * (HD / 2) * 2;
+        // sums of the splits in rising order (the RoPE kernel's order), two columns at a time and eight splits'
+        // loads in flight for each: one load per trip would cost a memory round trip per split
+        auto summed2 = [&](int col0, int col1, float &x, float &y) {
+            const float *p0 = rp.part + pt_index(col0, row, rp.M_all), *p1 = rp.part + pt_index(col1, row, rp.M_all);
+            x = 0.f;
+            y = 0.f;
+            for (int s0 = 0; s0 < rp.S; s0 += 8) {
+                float t0[8], t1[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const size_t o = (size_t)min(s0 + j, rp.S - 1) * rp.split_stride;
+                    t0[j] = p0[o];
+                    t1[j] = p1[o];
+                }
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    if (s0 + j < rp.S) {
+                        x += t0[j];
+                        y += t1[j];
+                    }
+            }
+        };
+        // The writing workgroup: its page id is asked for first, and every thread issues the loads of its K or V pair
+        // together with those of its Q pair (a thread without a pair repeats a valid column and drops the sums), so
+        // that the whole prologue is one memory round trip before the stores.
+        const int L_raw = a.prefix_len[d.seq_base + b];
+        const int it_new = (L >> 4) >> 1;                    // the key-pair iteration of position L
+        const bool writes = it_new >= a0 && it_new < a1 && seq_fits(a.kv, L_raw, 1);
+        int page = -1;
+        if (writes) page = a.kv.page_table[(size_t)(d.seq_base + b) * a.kv.pages_per_seq + (L >> 4)];
+        const int n_qp = a.group * (HD / 2);
+        const int wi = tid & (HD / 2 - 1);
+        const int wcol = (tid < HD / 2 ? rp.q_dim : rp.q_dim + rp.kv_dim) + g * HD + wi;
+        float wx, wy;
+        {
+            const int idx = min(tid, n_qp - 1);
+            const int hq = idx / (HD / 2), i = idx - hq * (HD / 2);
+            const int col = (g * a.group + hq) * HD + i;
+            float x, y;
+            summed2(col, col + HD / 2, x, y);
+            summed2(wcol, wcol + HD / 2, wx, wy);
+            const float c = cs[2 * i], sn = cs[2 * i + 1];
+            if (tid < n_qp) {
+                q_lds[hq * HD + i] = (bf16_t)(x * c - y * sn);
+                q_lds[hq * HD + i + HD / 2] = (bf16_t)(y * c + x * sn);
+            }
+        }
+        for (int idx = tid + 256; idx < n_qp; idx += 256) {          // more than four query heads per kv head
+            const int hq = idx / (HD / 2), i = idx - hq * (HD / 2);
+            const int col = (g * a.group + hq) * HD + i;
+            float x, y;
+            summed2(col, col + HD / 2, x, y);
+            const float c = cs[2 * i], sn = cs[2 * i + 1];
+            q_lds[hq * HD + i] = (bf16_t)(x * c - y * sn);
+            q_lds[hq * HD + i + HD / 2] = (bf16_t)(y * c + x * sn);
+        }
+        if (writes) {
+            const int slot = L & 15;
+            if (page_ok(a.kv, page) && tid < HD) {
+                if (tid < HD / 2) {
+                    const float c = cs[2 * wi], sn = cs[2 * wi + 1];
+                    bf16_t *kdst = (bf16_t *)a.kv.k_pages + k_page_offset(a.kv, page, g, slot, 0);
+                    kdst[wi] = (bf16_t)(wx * c - wy * sn);
+                    kdst[wi + HD / 2] = (bf16_t)(wy * c + wx * sn);
+                } else {
+                    bf16_t *vp = (bf16_t *)a.kv.v_pages;
+                    vp[v_page_offset(a.kv, page, g, slot, wi)] = (bf16_t)wx;
+                    vp[v_page_offset(a.kv, page, g, slot, wi + HD / 2)] = (bf16_t)wy;
+                }
+            }
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        }
+        __syncthreads();
+    }
+
     // ---- this wave's query tiles: Q fragments (B operand: lane = (q row, hd half of the k step)), row info
     bf16x8 qf[QT][8];
     int r_vis[QT], r_blk[QT];
@@ -349,7 +435,8 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
         r_vis[i] = ok ? ri.vis : 0;
         r_blk[i] = ok ? ri.blk : -2;
         if (ok) vis_min = min(vis_min, ri.vis);
-        const bf16_t *qp = a.q + (((size_t)b * d.R + r) * a.n_q + (g * a.group + hq)) * HD + 8 * lh;
+        const bf16_t *qp = ROPE ? q_lds + (ok ? f : 0) * HD + 8 * lh
+                                : a.q + (((size_t)b * d.R + r) * a.n_q + (g * a.group + hq)) * HD + 8 * lh;
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
             bf16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
@@ -736,14 +823,21 @@ AttnPlan plan_attention(int B, int n_kv, int group, int R, int nc, int max_keys)
     return p;
 }
 
+bool attention_rope_ok(RowDesc d, int group, int hd) {
+    return d.R == 1 && d.nc == 1 && d.nm == 0 && group >= 1 && group <= 32 && hd == HD;
+}
+
 size_t attn_partial_floats(int B, int n_kv, int group, int R, int hd, int splits) {
     return (size_t)B * n_kv * splits * group * R * (hd + 2);
 }
 
 void launch_attention_bf16(const bf16_t *q, KvView kv, const bf16_t *k_scr, const bf16_t *v_scr,
                            const int32_t *prefix_len, RowDesc d, int B, int n_q, const AttnPlan &p, float *part,
-                           bf16_t *out, int out_af, hipStream_t st) {
+                           bf16_t *out, int out_af, hipStream_t st, const AttnRope *rope) {
     AttnArgs a;
+    a.rp = AttnRope{};
+    const bool fused_rope = rope && rope->part && attention_rope_ok(d, n_q / kv.n_kv, kv.hd);
+    if (fused_rope) a.rp = *rope;
     a.out = out;
     a.out_af = out_af;
     a.lay = act_layout(B * d.R);
@@ -769,8 +863,9 @@ void launch_attention_bf16(const bf16_t *q, KvView kv, const bf16_t *k_scr, cons
     a.xcd_q = a.n_groups % 8 == 0 ? 1 : (a.n_groups < 8 && 8 % a.n_groups == 0) ? 8 / a.n_groups : 0;
     dim3 grid(a.n_groups * p.n_chunks, p.splits);
     if (a.xcd_q > 1) grid.x = 8 * ((p.n_chunks + a.xcd_q - 1) / a.xcd_q);
-    if (p.tiles_per_chunk == 4) attn_bf16_kernel<1, true><<<grid, 256, 0, st>>>(a);
-    else attn_bf16_kernel<1, false><<<grid, 256, 0, st>>>(a);
+    if (fused_rope) attn_bf16_kernel<1, false, true><<<grid, 256, 0, st>>>(a);
+    else if (p.tiles_per_chunk == 4) attn_bf16_kernel<1, true, false><<<grid, 256, 0, st>>>(a);
+    else attn_bf16_kernel<1, false, false><<<grid, 256, 0, st>>>(a);
 }
 
 void launch_attention_combine(const float *part, int B, int R, int n_q, int n_kv, int hd, int splits, bf16_t *out,

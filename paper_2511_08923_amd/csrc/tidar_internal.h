@@ -245,12 +245,27 @@ struct AttnPlan {
 AttnPlan plan_attention(int B, int n_kv, int group, int R, int nc, int max_keys);
 size_t attn_partial_floats(int B, int n_kv, int group, int R, int hd, int splits);
 
+// The one-token step (R = 1, no mask rows) skips the RoPE launch: the attention workgroups take the new row's Q, K
+// and V straight from the QKV projection's split-K partial sums (tiled layout, S splits), rotate Q and K by the
+// row's angles, and the workgroup whose key range ends at the new row writes K and V into the cache before it
+// reads that page.  part == nullptr: Q comes rotated from `q`, K/V are in place already.
+struct AttnRope {
+    const float *part;
+    int S;
+    size_t split_stride;
+    const float *rope_cs;      // [row][hd/2][(cos, sin)]
+    int M_all;                 // rows of the partial sums (= sequences of the call)
+    int q_dim, kv_dim;
+};
+
 // With one split the kernel writes the result to out (row-major [rows][n_q][hd], or, out_af != 0, the A-fragment
 // layout over B * R rows) and launch_attention_combine does nothing; with more it writes per-split partial
 // results to part, which launch_attention_combine folds into out.
 void launch_attention_bf16(const bf16_t *q, KvView kv, const bf16_t *k_scr, const bf16_t *v_scr,
                            const int32_t *prefix_len, RowDesc d, int B, int n_q, const AttnPlan &p, float *part,
-                           bf16_t *out, int out_af, hipStream_t st);
+                           bf16_t *out, int out_af, hipStream_t st, const AttnRope *rope = nullptr);
+// whether launch_attention_bf16 can take the new row from the partial sums for this row structure
+bool attention_rope_ok(RowDesc d, int group, int hd);
 void launch_attention_combine(const float *part, int B, int R, int n_q, int n_kv, int hd, int splits, bf16_t *out,
                               int out_af, hipStream_t st);
 void launch_attention_f32(const float *q, KvView kv, const float *k_scr, const float *v_scr,

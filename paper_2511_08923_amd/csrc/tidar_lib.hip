@@ -244,7 +244,8 @@ void gemm(tidar_ctx *ctx, const void *a, const void *w, float *out, int M, int N
 // Returns the number of key splits whose partial results wait in the workspace (1: o_out holds the result).  With
 // defer_combine the partial results are left for the consumer to fold.
 int attention(tidar_ctx *ctx, const Layout &l, char *ws, KvView kvv, const int32_t *prefix_len,
-              RowDesc d, int B, int max_keys, void *o_out, hipStream_t st, bool defer_combine = false) {
+              RowDesc d, int B, int max_keys, void *o_out, hipStream_t st, bool defer_combine = false,
+              const AttnRope *rope = nullptr) {
     const tidar_config &c = ctx->cfg;
     if (c.dtype == TIDAR_BF16) {
         AttnPlan ap = plan_attention(B, c.n_kv_heads, c.n_q_heads / c.n_kv_heads, d.R, d.nc, max_keys);
@@ -252,7 +253,7 @@ int attention(tidar_ctx *ctx, const Layout &l, char *ws, KvView kvv, const int32
             Prof p(ctx, KC_ATTN, st);
             launch_attention_bf16((const bf16_t *)(ws + l.q), kvv, (const bf16_t *)(ws + l.k_scr),
                                   (const bf16_t *)(ws + l.v_scr), prefix_len, d, B, c.n_q_heads, ap,
-                                  (float *)(ws + l.attn_part), (bf16_t *)o_out, 1, st);
+                                  (float *)(ws + l.attn_part), (bf16_t *)o_out, 1, st, rope);
         }
         if (ap.splits > 1 && !defer_combine) {
             Prof p(ctx, KC_ATTN_COMBINE, st);
@@ -295,7 +296,7 @@ void forward_rows(tidar_ctx *ctx, const tidar_weights *w, const tidar_kv_cache *
     int S_prev = 0;   // split count of the partial sums still waiting to be added to the residual stream
     // A forward of a few rows (the one-token step, very short blocks) is a chain of dependent launches whose kernels
     // are much shorter than the hand-over between them: there the RMSNorms and the split-KV combine are folded into
-    // the GEMMs that consume them (5-6 launches per layer instead of 9).
+    // the GEMMs that consume them (6 launches per layer instead of 9; 5 for the one-token step, see below).
     const bool fuse = c.dtype == TIDAR_BF16 && gemm_fuse_ok(M, q_dim + 2 * kv_dim, c.d_model) &&
                       gemm_fuse_ok(M, c.d_model, q_dim) && gemm_fuse_ok(M, 2 * c.d_ff, c.d_model);
     float *x_alt = (float *)(ws + l.x2);
@@ -335,12 +336,23 @@ void forward_rows(tidar_ctx *ctx, const tidar_weights *w, const tidar_kv_cache *
             }
             gemm(ctx, ws + l.xn, w->wqkv[layer], g_cur, M, q_dim + 2 * kv_dim, c.d_model, false, &S, st);
         }
-        {
+        // The one-token step has no RoPE launch either: its attention workgroups rotate the new row themselves
+        AttnRope rope = {};
+        if (fuse && attention_rope_ok(d, c.n_q_heads / c.n_kv_heads, c.head_dim)) {
+            rope.part = g_cur;
+            rope.S = S;
+            rope.split_stride = pt_split_stride(M, q_dim + 2 * kv_dim);
+            rope.rope_cs = (const float *)(ws + l.rope_cs);
+            rope.M_all = M;
+            rope.q_dim = q_dim;
+            rope.kv_dim = kv_dim;
+        } else {
             Prof p(ctx, KC_ROPE_KV, st);
             launch_rope_kv(c.dtype, g_cur, S, (const float *)(ws + l.rope_cs), prefix_len, d, B, c.n_q_heads, kvv,
                            ws + l.q, ws + l.k_scr, ws + l.v_scr, st);
         }
-        const int a_splits = attention(ctx, l, ws, kvv, prefix_len, d, B, max_keys, ws + l.o, st, fuse);
+        const int a_splits = attention(ctx, l, ws, kvv, prefix_len, d, B, max_keys, ws + l.o, st, fuse,
+                                       rope.part ? &rope : nullptr);
         if (fuse && a_splits > 1) {
             Prof p(ctx, KC_GEMM, st);
             GemmPlan gp = plan_gemm_bf16(M, c.d_model, q_dim, false);

@@ -553,6 +553,51 @@ def test_bf16_step_replayed_from_a_hip_graph_equals_host_launches(T, small):
         assert torch.equal(b[0], a1) and torch.equal(b[2], nxt1)
 
 
+@pytest.mark.parametrize("starts", [[62], [62, 77], [1, 15]])
+def test_bf16_one_token_steps_against_the_oracle_across_page_boundaries(T, small, starts):
+    """The 1-token step of up to four sequences has no RoPE launch: its attention workgroups build the new row's Q, K
+    and V from the QKV partial sums and the workgroup whose key range ends at the new position writes K/V into the
+    cache.  Teacher-forced steps from prefixes that end right before, at and after a page boundary (16 tokens per
+    page), ragged over the batch: logits within the bf16 tolerance, tokens equal up to near ties, the new cache row
+    within bf16 rounding of the oracle's, and every earlier slot of the page bit for bit what it was."""
+    eng, model = small
+    sh = TI.SMALL_GQA
+    B = len(starts)                          # 18 steps each: 62..79 and 77..94 cross 64 / 80; 1..18 and 15..32 start
+    sts, toks = [], []                       # in the first page
+
+    for b, P in enumerate(starts):
+        prompt = TI.make_prompt(sh, P, seed=300 + b)
+        st = model.new_state(256, seq_id=b)
+        tok, _ = model.causal_prefill(st, [int(t) for t in prompt[0]])
+        sts.append(st)
+        toks.append(tok)
+    n_tie = 0
+    for step in range(18):
+        for b in range(B):
+            load_oracle_state_into_engine(eng, sts[b], seq=b)
+        Ls = [st.L for st in sts]
+        before = [[[t.clone() for t in eng.read_cache(l, b, Ls[b])] for l in range(sh.n_layers)] for b in range(B)]
+        tok_in = torch.tensor(toks, dtype=torch.int32, device="cuda")
+        out, lg = eng.ar_step(tok_in, hint=max(Ls), want_logits=True)
+        torch.cuda.synchronize()
+        for b in range(B):
+            tok_o, lg_o = model.ar_step(sts[b], toks[b])
+            err = float((lg[b].cpu().double() - lg_o[0]).abs().max())
+            assert err < LOGIT_TOL, (step, b, err)
+            rows, bad = mismatch_rows(out[b:b + 1].cpu(), lg_o, err)
+            assert bad == 0, (step, b)
+            n_tie += len(rows)
+            assert int(eng.prefix_len[b]) == Ls[b] + 1
+            for l in range(sh.n_layers):
+                kk, vv = eng.read_cache(l, b, Ls[b] + 1)
+                assert torch.equal(kk[:Ls[b]], before[b][l][0]) and torch.equal(vv[:Ls[b]], before[b][l][1])
+                assert float((kk[Ls[b]].cpu().double() - sts[b].k[l][Ls[b]]).abs().max()) < 4e-2, (step, b, l)
+                assert float((vv[Ls[b]].cpu().double() - sts[b].v[l][Ls[b]]).abs().max()) < 4e-2, (step, b, l)
+            toks[b] = tok_o
+    assert n_tie <= 2
+    print(f"one-token steps, batch {B}: {n_tie} near-tie token(s) in {18 * B}", flush=True)
+
+
 def test_small_bf16_device_tidar_vs_device_ar(T, small):
     """On-device check 3 in bf16: streams agree until a row whose top-2 margin is within rounding."""
     eng, model = small
