@@ -808,6 +808,12 @@ AttnPlan plan_attention(int B, int n_kv, int group, int R, int nc, int max_keys)
     p.splits_bound = 2048 / base < 2 ? 2 : 2048 / base > 64 ? 64 : 2048 / base;
     int cap = (iters + 3) / 4;                // at least four key pairs per split
     if (cap > p.splits_bound) cap = p.splits_bound;
+    // A single query tile per kv head and few sequences (the one-token step up to batch 4): every workgroup is mostly
+    // prologue and epilogue, and its partial result is folded by each workgroup of the O projection.  No more splits
+    // than give every CU one workgroup - a grid a little above 256 leaves some CUs with two (batch 1, 4096 keys:
+    // 36 splits = 288 workgroups 3.75 ms per step, 32 splits 3.68; 12 288 keys: 3.94 -> 3.90) - as long as a split
+    // then stays short (batch 4 at 8192 keys: 8 splits of 32 iterations lose to 16 of 16, 5.14 against 5.02 ms).
+    if (TQ == 1 && base <= 32 && cap > 256 / base && iters <= 16 * (256 / base)) cap = 256 / base;
     int s = 1;
     double best = 0.0;
     for (int c = 1; c <= cap; ++c) {
