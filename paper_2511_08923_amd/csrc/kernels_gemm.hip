@@ -470,14 +470,15 @@ __global__ __launch_bounds__(256) void gemm_bf16_small_fused_kernel(FuseArgs f, 
 // MTA is 5: the second row half then repeats a tile whose results are dropped) of 128 columns.  WIDE: four waves
 // side by side, each over all CTL = MTA row tiles and 64 of the workgroup's 256 columns.  Chunk of K = 128 (8 k
 // steps); weight ring 16 k steps.
-template <int MTA, bool WIDE>
+template <int MTA, bool WIDE, int NT = 2>
 __global__ __launch_bounds__(256) void gemm_bf16_large_kernel(const bf16_t *__restrict__ a,
                                                               const bf16_t *__restrict__ w, float *__restrict__ out,
                                                               int M, int N, int K, int splits, int epi,
                                                               int swz_p, int swz_c, int n_pass, int n_colblk,
                                                               ChooseArgs ch) {
-    constexpr int NT = 2, KS = 8;
-    constexpr bool BIG = WIDE && MTA >= 6;       // the many-row variants: registers go to the accumulators
+    constexpr int KS = 8;
+    static_assert(NT == 2 || (NT == 1 && WIDE), "one column tile per wave only with the waves side by side");
+    constexpr bool BIG = WIDE && MTA >= 6 && NT == 2;   // the many-row variants: registers go to the accumulators
     constexpr int PFK = BIG ? KS : 2 * KS;       // weight ring depth in k steps: one chunk or two
     constexpr int CTL = WIDE ? MTA : (MTA == 5) ? 9 : 2 * MTA;
     // Many row passes: the (pass, column block) plane is cut into super-tiles of swz_p x swz_c workgroups, each
@@ -498,7 +499,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_large_kernel(const bf16_t *__re
     constexpr int PIECES = CTL * KS * 64;        // 16-byte pieces per chunk
     constexpr int STAGE = (PIECES + 255) / 256;
     constexpr int FR = KS * MTA;                 // A fragments a wave consumes per chunk
-    constexpr int AFD = 3;                       // LDS -> register prefetch distance in fragments
+    constexpr int AFD = NT == 1 ? 6 : 3;         // LDS -> register prefetch distance in fragments (NT MFMAs each)
     static_assert(2 * STAGE <= FR, "one staging piece is stored after every other fragment");
     extern __shared__ __attribute__((aligned(16))) unsigned char gemm_smem[];
     bf16x8 *lds = reinterpret_cast<bf16x8 *>(gemm_smem);      // [2][KS][CTL][64]
@@ -772,11 +773,11 @@ void launch_small(const bf16_t *a, const bf16_t *w, float *out, int M, int N, in
     gemm_bf16_small_kernel<MT, PFK><<<grid, 256, 0, st>>>(a, w, out, M, N, K, p.splits, row_major, ch);
 }
 
-template <int MTA, bool WIDE>
+template <int MTA, bool WIDE, int NT = 2>
 void launch_large(const bf16_t *a, const bf16_t *w, float *out, int M, int N, int K, const GemmPlan &p, int epi,
                   hipStream_t st, const ChooseArgs &ch) {
     constexpr int CTL = WIDE ? MTA : (MTA == 5) ? 9 : 2 * MTA;
-    constexpr int BN = WIDE ? 256 : 128;
+    constexpr int BN = WIDE ? 128 * NT : 128;
     int m_tiles = (M + 31) / 32;
     dim3 grid((N + BN - 1) / BN, p.splits, (m_tiles + CTL - 1) / CTL);
     const int n_colblk = grid.x, n_pass = grid.z;
@@ -787,17 +788,19 @@ void launch_large(const bf16_t *a, const bf16_t *w, float *out, int M, int N, in
         const int n_st = ((n_pass + swz_p - 1) / swz_p) * ((n_colblk + swz_c - 1) / swz_c);
         grid = dim3(8 * ((n_st + 7) / 8) * swz_p * swz_c, p.splits, 1);
     }
-    constexpr size_t SMEM = (size_t)2 * CTL * 8 * 1024;
+    // two staging buffers of a chunk's A tiles; the epilogue's per-wave transposition patches (4 x 32 x 36 floats)
+    // reuse the same memory and need 18 KiB of it
+    constexpr size_t SMEM = (size_t)2 * CTL * 8 * 1024 > 4 * 32 * 36 * 4 ? (size_t)2 * CTL * 8 * 1024 : 4 * 32 * 36 * 4;
     // LDS above 64 KiB has to be granted per kernel, on every device the kernel is launched on
     static bool attr_set[64] = {};
     int dev = 0;
     (void)hipGetDevice(&dev);
     if (dev < 0 || dev >= 64 || !attr_set[dev]) {
-        (void)hipFuncSetAttribute((const void *)gemm_bf16_large_kernel<MTA, WIDE>,
+        (void)hipFuncSetAttribute((const void *)gemm_bf16_large_kernel<MTA, WIDE, NT>,
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)SMEM);
         if (dev >= 0 && dev < 64) attr_set[dev] = true;
     }
-    gemm_bf16_large_kernel<MTA, WIDE><<<grid, 256, SMEM, st>>>(a, w, out, M, N, K, p.splits, epi, swz_p, swz_c, n_pass,
+    gemm_bf16_large_kernel<MTA, WIDE, NT><<<grid, 256, SMEM, st>>>(a, w, out, M, N, K, p.splits, epi, swz_p, swz_c, n_pass,
                                                                n_colblk, ch);
 }
 
@@ -847,6 +850,16 @@ GemmPlan plan_gemm_bf16(int M, int N, int K, bool force_single_split) {
         const int per_pass = row_split ? (t + 1) / 2 : t;
         p.mt = per_pass <= 2 ? 1 : per_pass <= 4 ? 2 : per_pass <= 6 ? 3 : 5;      // per wave (wide kernel)
         int ctl = p.mt == 5 ? 9 : 2 * p.mt;
+        // Two row passes of three to five tiles (129-320 rows): the four waves side by side, each over all row tiles of
+        // the pass and one 32-column tile of the workgroup's 128 columns - at 272 rows five MFMAs per wave and k step
+        // where the 2 x 2 arrangement runs six (two passes of six tile slots for nine tiles), and no weight fragment
+        // is loaded twice
+        if (row_split && t < 16) {
+            p.wide = 1;
+            p.nt = 1;
+            p.mt = per_pass;
+            ctl = per_pass;
+        }
         // many column blocks, one split, more than five row tiles: 256-column workgroups over five row tiles
         // (four waves side by side, no weight fragment loaded twice) in two or more row passes.  Only when the
         // whole grid is resident at once: the passes of a column block then run together and the second read
@@ -855,6 +868,7 @@ GemmPlan plan_gemm_bf16(int M, int N, int K, bool force_single_split) {
         const int wide_wgs = ((N + 255) / 256) * ((t + 4) / 5);
         if (splits == 1 && wgs >= 128 && t > 5 && wide_wgs <= 256) {
             p.wide = 1;
+            p.nt = 2;
             p.mt = 5;
             ctl = 5;
         } else if (splits == 1 && wgs >= 512 && t > 5) {
@@ -862,6 +876,7 @@ GemmPlan plan_gemm_bf16(int M, int N, int K, bool force_single_split) {
             // dealt to the XCDs in super-tiles the passes of a column block run on one XCD at about the same
             // time and share the weights through its L2: 436 -> 402 us at 272 rows.
             p.wide = 1;
+            p.nt = 2;
             p.mt = 5;
             ctl = 5;
             p.swz = 4;
@@ -874,6 +889,7 @@ GemmPlan plan_gemm_bf16(int M, int N, int K, bool force_single_split) {
         // than the sharing gains).
         if (t >= 16) {
             p.wide = 1;
+            p.nt = 2;
             const int passes = (t + 7) / 8;
             p.mt = ctl = (t + passes - 1) / passes;      // 6, 7 or 8 row tiles per pass: the passes come out even
             p.swz = (N + 255) / 256 >= 256 ? 4 : 0;
@@ -909,6 +925,22 @@ void launch_gemm_bf16(const bf16_t *a, const bf16_t *w, float *out, int M, int N
     if (M <= 32) {
         if (p.mt == 1) launch_small<1, 16>(a, w, out, M, N, K, p, out_row_major, st, ch);
         else launch_small<2, 8>(a, w, out, M, N, K, p, out_row_major, st, ch);
+    } else if (p.wide && p.nt == 1 && p.mt == 1 && out_row_major != GEMM_EPI_ARGMAX) {
+        launch_large<1, true, 1>(a, w, out, M, N, K, p, out_row_major, st, ch);
+    } else if (p.wide && p.nt == 1 && p.mt == 2 && out_row_major != GEMM_EPI_ARGMAX) {
+        launch_large<2, true, 1>(a, w, out, M, N, K, p, out_row_major, st, ch);
+    } else if (p.wide && p.nt == 1 && p.mt == 3 && out_row_major != GEMM_EPI_ARGMAX) {
+        launch_large<3, true, 1>(a, w, out, M, N, K, p, out_row_major, st, ch);
+    } else if (p.wide && p.nt == 1 && p.mt == 4 && out_row_major != GEMM_EPI_ARGMAX) {
+        launch_large<4, true, 1>(a, w, out, M, N, K, p, out_row_major, st, ch);
+    } else if (p.wide && p.nt == 1 && p.mt == 5 && out_row_major != GEMM_EPI_ARGMAX) {
+        launch_large<5, true, 1>(a, w, out, M, N, K, p, out_row_major, st, ch);
+    } else if (p.wide && p.nt == 1 && p.mt == 6 && out_row_major != GEMM_EPI_ARGMAX) {
+        launch_large<6, true, 1>(a, w, out, M, N, K, p, out_row_major, st, ch);
+    } else if (p.wide && p.nt == 1 && p.mt == 7 && out_row_major != GEMM_EPI_ARGMAX) {
+        launch_large<7, true, 1>(a, w, out, M, N, K, p, out_row_major, st, ch);
+    } else if (p.wide && p.nt == 1 && out_row_major != GEMM_EPI_ARGMAX) {
+        launch_large<8, true, 1>(a, w, out, M, N, K, p, out_row_major, st, ch);
     } else if (p.wide && p.mt == 8) {
         launch_large<8, true>(a, w, out, M, N, K, p, out_row_major, st, ch);
     } else if (p.wide && p.mt == 7) {

@@ -47,6 +47,10 @@ def _gemm(T, ctx, a, w):
                                    # row passes: 3 tiles as 2+1, 5 as 3+2, 7 as 4+3, 12 as 6+6; one tile (no row split)
                                    (65, 4096, 2048), (160, 1536, 1536), (200, 4096, 1024), (384, 2048, 4096),
                                    (40, 6144, 1024),
+                                   # two row passes with the waves side by side, one column tile each: passes of
+                                   # 1 (one real row in the second), 2, 6+5, 7+6 and 8+7 tiles, ragged N and K
+                                   (33, 784, 608), (100, 1040, 1056), (350, 528, 288), (416, 784, 608),
+                                   (470, 1040, 1056),
                                    # 512 rows and more: 256 x 256 workgroup tiles (eight row tiles per wave, half-size
                                    # staging ring), whole and ragged row passes, split K, ragged column block, an
                                    # odd chunk count (K = 384), and a grid wide enough for the XCD super-tiles
