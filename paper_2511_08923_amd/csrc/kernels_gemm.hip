@@ -681,17 +681,22 @@ __global__ __launch_bounds__(256) void gemm_bf16_large_kernel(const bf16_t *__re
         return;
     }
     if (epi == GEMM_EPI_ARGMAX) {
-        // a lane walks its 32 columns of the wave's two tiles in rising order (strict > keeps the lowest column
-        // of a tie), then the two half-waves, which hold the same rows, are folded
+        // a lane walks its 16 columns of each of the wave's tiles in rising order (strict > keeps the lowest column
+        // of a tie), then the two half-waves, which hold the same rows, are folded.  A column group is 64 columns:
+        // the wave's two tiles, or (NT = 1) the tiles of two neighbouring waves, folded through LDS.
         const int G = (t32 + 1) >> 1;
         float *pmax = out;
         int *pidx = (int *)(out + (size_t)G * M);
+        float bests[MTA];
+        int bis[MTA];
 #pragma unroll
         for (int mt = 0; mt < MTA; ++mt) {
             const int tile_r = mh * MTA + mt;
-            if (tile_r >= ct_here) continue;      // wave-uniform
             float best = -INFINITY;
             int bi = tile0 * 32 + 4 * lh;
+            bests[mt] = best;
+            bis[mt] = bi;
+            if (tile_r >= ct_here) continue;      // wave-uniform
             const RowChoice rc = row_choice(ch, (mt_base + tile_r) * 32 + lq, M);
             if (__any(rc.noisy || rc.sel >= 0)) {     // a tile that holds rows a token is taken from (wave-uniform)
 #pragma unroll
@@ -726,10 +731,39 @@ __global__ __launch_bounds__(256) void gemm_bf16_large_kernel(const bf16_t *__re
                 best = ob;
                 bi = oi;
             }
+            bests[mt] = best;
+            bis[mt] = bi;
+        }
+        if constexpr (NT == 1) {
+            // the odd wave of a pair hands its result to the even one (the staging buffers are free by now)
+            float *rb = reinterpret_cast<float *>(gemm_smem);
+            int *ri = reinterpret_cast<int *>(gemm_smem) + 4 * MTA * 32;
+            if (lh == 0) {
+#pragma unroll
+                for (int mt = 0; mt < MTA; ++mt) {
+                    rb[(wave * MTA + mt) * 32 + lq] = bests[mt];
+                    ri[(wave * MTA + mt) * 32 + lq] = bis[mt];
+                }
+            }
+            __syncthreads();
+            if (wave & 1) return;
+#pragma unroll
+            for (int mt = 0; mt < MTA; ++mt) {
+                const float ob = rb[((wave + 1) * MTA + mt) * 32 + lq];
+                const int oi = ri[((wave + 1) * MTA + mt) * 32 + lq];
+                if (ob > bests[mt] || (ob == bests[mt] && oi < bis[mt])) {
+                    bests[mt] = ob;
+                    bis[mt] = oi;
+                }
+            }
+        }
+#pragma unroll
+        for (int mt = 0; mt < MTA; ++mt) {
+            const int tile_r = mh * MTA + mt;
             const int row = (mt_base + tile_r) * 32 + lq;
-            if (lh == 0 && row < M && tile0 < t32) {
-                pmax[(size_t)(tile0 >> 1) * M + row] = best;
-                pidx[(size_t)(tile0 >> 1) * M + row] = bi;
+            if (tile_r < ct_here && lh == 0 && row < M && tile0 < t32) {
+                pmax[(size_t)(tile0 >> 1) * M + row] = bests[mt];
+                pidx[(size_t)(tile0 >> 1) * M + row] = bis[mt];
             }
         }
         return;
@@ -866,7 +900,17 @@ GemmPlan plan_gemm_bf16(int M, int N, int K, bool force_single_split) {
         // of its weights hits L2 (measured on the LM head, whose grid takes several rounds: 30 % slower in
         // plain launch order)
         const int wide_wgs = ((N + 255) / 256) * ((t + 4) / 5);
-        if (splits == 1 && wgs >= 128 && t > 5 && wide_wgs <= 256) {
+        if (splits == 1 && wgs >= 128 && (t == 6 || t == 7)) {
+            // Six or seven row tiles, one split, many column blocks (gate/up and the LM head at 161-224 rows): one
+            // row pass of 128-column workgroups, every wave over all row tiles and one column tile - t MFMAs per
+            // wave and k step where two passes of five tile slots ran ten, the weights read once.  Measured per
+            // GEMM: -12 % at six tiles, -10 % at seven, nothing at eight, +5 % at nine (a workgroup then stages all
+            // of A for half as many columns), so from eight tiles on the two passes stay.
+            p.wide = 1;
+            p.nt = 1;
+            p.mt = t;
+            ctl = t;
+        } else if (splits == 1 && wgs >= 128 && t > 5 && wide_wgs <= 256) {
             p.wide = 1;
             p.nt = 2;
             p.mt = 5;
@@ -925,21 +969,21 @@ void launch_gemm_bf16(const bf16_t *a, const bf16_t *w, float *out, int M, int N
     if (M <= 32) {
         if (p.mt == 1) launch_small<1, 16>(a, w, out, M, N, K, p, out_row_major, st, ch);
         else launch_small<2, 8>(a, w, out, M, N, K, p, out_row_major, st, ch);
-    } else if (p.wide && p.nt == 1 && p.mt == 1 && out_row_major != GEMM_EPI_ARGMAX) {
+    } else if (p.wide && p.nt == 1 && p.mt == 1) {
         launch_large<1, true, 1>(a, w, out, M, N, K, p, out_row_major, st, ch);
-    } else if (p.wide && p.nt == 1 && p.mt == 2 && out_row_major != GEMM_EPI_ARGMAX) {
+    } else if (p.wide && p.nt == 1 && p.mt == 2) {
         launch_large<2, true, 1>(a, w, out, M, N, K, p, out_row_major, st, ch);
-    } else if (p.wide && p.nt == 1 && p.mt == 3 && out_row_major != GEMM_EPI_ARGMAX) {
+    } else if (p.wide && p.nt == 1 && p.mt == 3) {
         launch_large<3, true, 1>(a, w, out, M, N, K, p, out_row_major, st, ch);
-    } else if (p.wide && p.nt == 1 && p.mt == 4 && out_row_major != GEMM_EPI_ARGMAX) {
+    } else if (p.wide && p.nt == 1 && p.mt == 4) {
         launch_large<4, true, 1>(a, w, out, M, N, K, p, out_row_major, st, ch);
-    } else if (p.wide && p.nt == 1 && p.mt == 5 && out_row_major != GEMM_EPI_ARGMAX) {
+    } else if (p.wide && p.nt == 1 && p.mt == 5) {
         launch_large<5, true, 1>(a, w, out, M, N, K, p, out_row_major, st, ch);
-    } else if (p.wide && p.nt == 1 && p.mt == 6 && out_row_major != GEMM_EPI_ARGMAX) {
+    } else if (p.wide && p.nt == 1 && p.mt == 6) {
         launch_large<6, true, 1>(a, w, out, M, N, K, p, out_row_major, st, ch);
-    } else if (p.wide && p.nt == 1 && p.mt == 7 && out_row_major != GEMM_EPI_ARGMAX) {
+    } else if (p.wide && p.nt == 1 && p.mt == 7) {
         launch_large<7, true, 1>(a, w, out, M, N, K, p, out_row_major, st, ch);
-    } else if (p.wide && p.nt == 1 && out_row_major != GEMM_EPI_ARGMAX) {
+    } else if (p.wide && p.nt == 1) {
         launch_large<8, true, 1>(a, w, out, M, N, K, p, out_row_major, st, ch);
     } else if (p.wide && p.mt == 8) {
         launch_large<8, true>(a, w, out, M, N, K, p, out_row_major, st, ch);

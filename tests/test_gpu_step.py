@@ -705,6 +705,38 @@ def test_1p5b_shape_two_layers_prefill_and_steps_vs_oracle(T):
     eng.close()
 
 
+@pytest.mark.parametrize("k", [13, 14])
+def test_1p5b_shape_two_layers_six_and_seven_row_tiles(T, k):
+    """k = 13 and 14 give 182 and 210 rows: six and seven 32-row tiles, which gate/up and the LM head (many column
+    blocks, one split) run as a single row pass with one column tile per wave, the LM head's argmax epilogue folding
+    two waves' tiles into one 64-column group.  One teacher-forced step against the oracle through the logits path,
+    then the same step without logits (SwiGLU and argmax epilogues of that arrangement): identical outputs."""
+    sh = TI.SHAPE_1P5B.with_layers(2)
+    w = TI.make_weights(sh, seed=3, dtype=torch.bfloat16)
+    eng = T.Engine(sh, w, dtype=T.TIDAR_BF16, max_k=16, max_batch=1, max_seq_len=256)
+    model = O.OracleModel(sh, w, dtype=torch.float64, bf16_faithful=True)
+    P = 90
+    prompt = TI.make_prompt(sh, P, seed=40 + k)
+    st = model.new_state(256)
+    d_o, _ = model.prefill(st, [int(t) for t in prompt[0]], k)
+    load_oracle_state_into_engine(eng, st)
+    L = st.L
+    drafts = torch.tensor([list(d_o)], dtype=torch.int32, device="cuda")
+    a_o, acc_o, nxt_o, lg_o = model.tidar_step(st, list(d_o))
+    a, acc, nxt, lg = eng.step(drafts, k, hint=L, want_logits=True)
+    torch.cuda.synchronize()
+    par = StepParity(f"1.5b-shape 2 layers k={k}")
+    err, rms, rows = par.check(k, lg[0].cpu(), dev_out(eng, a, acc, nxt), lg_o, (a_o, acc_o, nxt_o, st.L), 3e-2)
+    print(f"  k={k}: max logit err {err:.2e}, near-tie rows {len(rows)}", flush=True)
+    got = (int(a[0]), acc[0].tolist(), nxt[0].tolist())
+    eng.prefix_len[:1].fill_(L)
+    a2, acc2, nxt2, _ = eng.step(drafts, k, hint=L)
+    torch.cuda.synchronize()
+    assert (int(a2[0]), acc2[0, :got[0]].tolist(), nxt2[0].tolist()) == (got[0], got[1][:got[0]], got[2])
+    par.report(min_exact=0)
+    eng.close()
+
+
 # ----------------------------------------------------------------------------- batch sweep shapes (config 5)
 @pytest.mark.parametrize("B,k", [(4, 16), (8, 8), (32, 4)])
 def test_small_bf16_batched_steps_match_oracle(T, B, k):
