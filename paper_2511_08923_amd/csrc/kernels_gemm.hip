@@ -17,8 +17,11 @@
 //     fragments through two register rings.  M > 32: 32x32x16 MFMA (on gfx950 it issues at twice the rate of
 //     16x16x32: measured 2.2 vs 1.2 PFLOP/s), A staged through LDS once per workgroup and prefetched into
 //     registers ahead of the MFMAs; 4 waves either as a 2 x 2 grid over 128 columns (two row halves x two
-//     64-column groups) or, for single-split grids that are resident all at once, side by side over 256 columns
-//     (no weight fragment is then loaded by two waves).  The weight fragment is the MFMA's first operand, so the
+//     64-column groups: launches without a row split), or side by side, every wave over all row tiles of the pass
+//     (no weight fragment is then loaded by two waves): over 256 columns with two column tiles per wave for
+//     single-split grids that are resident all at once and for the many-row class, over 128 columns with one
+//     column tile per wave for the two-pass launches of 33-480 rows (no padded tile slots; twice the LDS fragment
+//     reads per MFMA, which the LDS has room for).  The weight fragment is the MFMA's first operand, so the
 //     accumulators hold the output transposed (lane = row): every epilogue starts from that.
 //   * split-K over blockIdx.y works in units of 512 k, row passes over blockIdx.z; up to 480 rows the split count
 //     depends on (N, K) and the kernel class (M <= 32 or not) only, so the partial-sum grouping of a row does not
@@ -468,8 +471,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_small_fused_kernel(FuseArgs f, 
 // ------------------------------------------------------------------ 32 < M: 32x32x16 MFMA, A through LDS
 // MTA: 32-row tiles per wave.  2 x 2 waves (WIDE false): the workgroup pass covers CTL = 2*MTA row tiles (9 when
 // MTA is 5: the second row half then repeats a tile whose results are dropped) of 128 columns.  WIDE: four waves
-// side by side, each over all CTL = MTA row tiles and 64 of the workgroup's 256 columns.  Chunk of K = 128 (8 k
-// steps); weight ring 16 k steps.
+// side by side, each over all CTL = MTA row tiles and NT 32-column tiles of the workgroup's 128 * NT columns.
+// Chunk of K = 128 (8 k steps); weight ring 16 k steps.
 template <int MTA, bool WIDE, int NT = 2>
 __global__ __launch_bounds__(256) void gemm_bf16_large_kernel(const bf16_t *__restrict__ a,
                                                               const bf16_t *__restrict__ w, float *__restrict__ out,
