@@ -553,6 +553,58 @@ def test_bf16_step_replayed_from_a_hip_graph_equals_host_launches(T, small):
         assert torch.equal(b[0], a1) and torch.equal(b[2], nxt1)
 
 
+def test_bf16_one_token_step_replayed_from_a_hip_graph_equals_host_launches(T, small):
+    """The captured one-token step (no RoPE launch: its attention workgroups write the new K/V row themselves) is
+    replayed over a growing prefix - the token fed back on the device, the prefix length advanced by the step
+    itself - and across a page boundary; tokens and the cache rows written must be those of host launches."""
+    eng, _ = small
+    sh = TI.SMALL_GQA
+    P, n = 59, 12                                   # positions 59..70: the page boundary at 64 lies inside
+    prompt = TI.make_prompt(sh, P, seed=93)
+    first, _ = eng.prefill(prompt, 4)
+    torch.cuda.synchronize()
+    tok0 = first[:, 0].contiguous()
+    want, tok = [], tok0.clone()
+    for i in range(n):                              # host launches
+        out, _ = eng.ar_step(tok, hint=P + n)
+        torch.cuda.synchronize()
+        want.append(int(out[0]))
+        tok = out.clone()
+    cache_want = [[t.clone() for t in eng.read_cache(l, 0, P + n)] for l in range(sh.n_layers)]
+    tin = tok0.clone()
+    tout = torch.empty(1, dtype=torch.int32, device="cuda")
+    eng.prefix_len[:1].fill_(P)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        eng.ar_step(tin, hint=P + n, out=tout)      # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        eng.ar_step(tin, hint=P + n, out=tout)
+        tin.copy_(tout)
+    for rep in range(2):
+        tin.copy_(tok0)
+        eng.prefix_len[:1].fill_(P)
+        for l in range(sh.n_layers):                # the rows the replays must write are cleared first
+            eng.k_pages[l].zero_()
+            eng.v_pages[l].zero_()
+            eng.write_cache(l, 0, cache_want[l][0][:P], cache_want[l][1][:P])
+        got = []
+        for i in range(n):
+            g.replay()
+            if i % 5 == 2:
+                torch.cuda.synchronize()            # host synchronisations between some of the replays
+            got.append(tout.clone())
+        torch.cuda.synchronize()
+        assert [int(t[0]) for t in got] == want, rep
+        assert int(eng.prefix_len[0]) == P + n
+        for l in range(sh.n_layers):
+            kk, vv = eng.read_cache(l, 0, P + n)
+            assert torch.equal(kk, cache_want[l][0]) and torch.equal(vv, cache_want[l][1]), (rep, l)
+
+
 @pytest.mark.parametrize("starts", [[62], [62, 77], [1, 15]])
 def test_bf16_one_token_steps_against_the_oracle_across_page_boundaries(T, small, starts):
     """The 1-token step of up to four sequences has no RoPE launch: its attention workgroups build the new row's Q, K
