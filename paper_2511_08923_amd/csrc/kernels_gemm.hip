@@ -473,14 +473,16 @@ __global__ __launch_bounds__(256) void gemm_bf16_small_fused_kernel(FuseArgs f, 
 // MTA is 5: the second row half then repeats a tile whose results are dropped) of 128 columns.  WIDE: four waves
 // side by side, each over all CTL = MTA row tiles and NT 32-column tiles of the workgroup's 128 * NT columns.
 // Chunk of K = 128 (8 k steps); weight ring 16 k steps.
-template <int MTA, bool WIDE, int NT = 2>
-__global__ __launch_bounds__(256) void gemm_bf16_large_kernel(const bf16_t *__restrict__ a,
+template <int MTA, bool WIDE, int NT = 2, int NW = 4>
+__global__ __launch_bounds__(64 * NW) void gemm_bf16_large_kernel(const bf16_t *__restrict__ a,
                                                               const bf16_t *__restrict__ w, float *__restrict__ out,
                                                               int M, int N, int K, int splits, int epi,
                                                               int swz_p, int swz_c, int n_pass, int n_colblk,
                                                               ChooseArgs ch) {
     constexpr int KS = 8;
     static_assert(NT == 2 || (NT == 1 && WIDE), "one column tile per wave only with the waves side by side");
+    static_assert(NW == 4 || (NW == 8 && WIDE && NT == 1), "eight waves only side by side with one column tile each");
+    constexpr int THREADS = 64 * NW;
     constexpr bool BIG = WIDE && MTA >= 6 && NT == 2;   // the many-row variants: registers go to the accumulators
     constexpr int PFK = BIG ? KS : 2 * KS;       // weight ring depth in k steps: one chunk or two
     constexpr int CTL = WIDE ? MTA : (MTA == 5) ? 9 : 2 * MTA;
@@ -500,7 +502,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_large_kernel(const bf16_t *__re
         if (bz >= n_pass || bx >= n_colblk) return;
     }
     constexpr int PIECES = CTL * KS * 64;        // 16-byte pieces per chunk
-    constexpr int STAGE = (PIECES + 255) / 256;
+    constexpr int STAGE = (PIECES + THREADS - 1) / THREADS;
     constexpr int FR = KS * MTA;                 // A fragments a wave consumes per chunk
     constexpr int AFD = NT == 1 ? 6 : 3;         // LDS -> register prefetch distance in fragments (NT MFMAs each)
     static_assert(2 * STAGE <= FR, "one staging piece is stored after every other fragment");
@@ -516,7 +518,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_large_kernel(const bf16_t *__re
     const SplitRange sr32 = split_range(K, splits, blockIdx.y);
     const int q0 = sr32.q0 * 2, q1 = min(sr32.q1 * 2, q_total);
     const int c0 = q0 / KS, c1 = (q1 + KS - 1) / KS;
-    const int tile0 = (bx * (WIDE ? 4 : 2) + ng) * NT;   // first 32-column tile of this wave
+    const int tile0 = (bx * (WIDE ? NW : 2) + ng) * NT;  // first 32-column tile of this wave
     const __amdgpu_buffer_rsrc_t ra = make_rsrc(a, (size_t)q_total * m_tiles * 1024);
     const __amdgpu_buffer_rsrc_t rw = make_rsrc(w, (size_t)t32 * 32 * K * 2);
 
@@ -528,7 +530,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_large_kernel(const bf16_t *__re
         return buf_load(rw, (q < q1 && w_off[j] != OOB) ? w_off[j] + q * w_step : OOB);
     };
 
-    // A staging: piece p = tid + s*256 of the chunk = lane `lane` of fragment (wave + 4s) -> (k step, row tile).
+    // A staging: piece p = tid + s*THREADS of the chunk = lane `lane` of fragment (wave + NW*s) -> (k step, row tile).
     // The fragment index is wave-uniform, so its address lives in scalar registers (the buffer load's scalar
     // offset) and only lane*16, or the out-of-bounds offset for a fragment that does not exist, in a VGPR.
     const int wv = __builtin_amdgcn_readfirstlane(wave);
@@ -541,7 +543,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_large_kernel(const bf16_t *__re
     static_assert(!HALF || (STAGE % 2 == 0 && 4 * STAGE <= FR), "two events per staging register and chunk");
     bf16x8 stage[SR];
     auto load_a1 = [&](int s, int c) {          // piece s of chunk c -> staging register s % SR
-        const int i = wv + 4 * s;
+        const int i = wv + NW * s;
         const int ks = i / CTL, ct = i % CTL;
         const bool ok = i < CTL * KS && ct < ct_here && c < c1;
         stage[s % SR] = __builtin_bit_cast(
@@ -549,7 +551,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_large_kernel(const bf16_t *__re
                                                           (ks * m_tiles + mt_base + ct) * 1024 + c * a_chunk_step, 0));
     };
     auto store_a1 = [&](int s, int buf) {
-        if (STAGE * 256 == PIECES || tid + s * 256 < PIECES) lds[buf * PIECES + tid + s * 256] = stage[s % SR];
+        if (STAGE * THREADS == PIECES || tid + s * THREADS < PIECES) lds[buf * PIECES + tid + s * THREADS] = stage[s % SR];
     };
 
     f32x16 acc[MTA][NT];
@@ -740,7 +742,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_large_kernel(const bf16_t *__re
         if constexpr (NT == 1) {
             // the odd wave of a pair hands its result to the even one (the staging buffers are free by now)
             float *rb = reinterpret_cast<float *>(gemm_smem);
-            int *ri = reinterpret_cast<int *>(gemm_smem) + 4 * MTA * 32;
+            int *ri = reinterpret_cast<int *>(gemm_smem) + NW * MTA * 32;
             if (lh == 0) {
 #pragma unroll
                 for (int mt = 0; mt < MTA; ++mt) {
@@ -810,11 +812,11 @@ void launch_small(const bf16_t *a, const bf16_t *w, float *out, int M, int N, in
     gemm_bf16_small_kernel<MT, PFK><<<grid, 256, 0, st>>>(a, w, out, M, N, K, p.splits, row_major, ch);
 }
 
-template <int MTA, bool WIDE, int NT = 2>
+template <int MTA, bool WIDE, int NT = 2, int NW = 4>
 void launch_large(const bf16_t *a, const bf16_t *w, float *out, int M, int N, int K, const GemmPlan &p, int epi,
                   hipStream_t st, const ChooseArgs &ch) {
     constexpr int CTL = WIDE ? MTA : (MTA == 5) ? 9 : 2 * MTA;
-    constexpr int BN = WIDE ? 128 * NT : 128;
+    constexpr int BN = WIDE ? 32 * NW * NT : 128;
     int m_tiles = (M + 31) / 32;
     dim3 grid((N + BN - 1) / BN, p.splits, (m_tiles + CTL - 1) / CTL);
     const int n_colblk = grid.x, n_pass = grid.z;
@@ -827,17 +829,18 @@ void launch_large(const bf16_t *a, const bf16_t *w, float *out, int M, int N, in
     }
     // two staging buffers of a chunk's A tiles; the epilogue's per-wave transposition patches (4 x 32 x 36 floats)
     // reuse the same memory and need 18 KiB of it
-    constexpr size_t SMEM = (size_t)2 * CTL * 8 * 1024 > 4 * 32 * 36 * 4 ? (size_t)2 * CTL * 8 * 1024 : 4 * 32 * 36 * 4;
+    constexpr size_t PATCH = (size_t)NW * 32 * 36 * 4;
+    constexpr size_t SMEM = (size_t)2 * CTL * 8 * 1024 > PATCH ? (size_t)2 * CTL * 8 * 1024 : PATCH;
     // LDS above 64 KiB has to be granted per kernel, on every device the kernel is launched on
     static bool attr_set[64] = {};
     int dev = 0;
     (void)hipGetDevice(&dev);
     if (dev < 0 || dev >= 64 || !attr_set[dev]) {
-        (void)hipFuncSetAttribute((const void *)gemm_bf16_large_kernel<MTA, WIDE, NT>,
+        (void)hipFuncSetAttribute((const void *)gemm_bf16_large_kernel<MTA, WIDE, NT, NW>,
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)SMEM);
         if (dev >= 0 && dev < 64) attr_set[dev] = true;
     }
-    gemm_bf16_large_kernel<MTA, WIDE, NT><<<grid, 256, SMEM, st>>>(a, w, out, M, N, K, p.splits, epi, swz_p, swz_c, n_pass,
+    gemm_bf16_large_kernel<MTA, WIDE, NT, NW><<<grid, 64 * NW, SMEM, st>>>(a, w, out, M, N, K, p.splits, epi, swz_p, swz_c, n_pass,
                                                                n_colblk, ch);
 }
 
@@ -861,6 +864,7 @@ GemmPlan plan_gemm_bf16(int M, int N, int K, bool force_single_split) {
     p.nt = 2;
     p.bk = 128;
     p.wide = 0;
+    p.nw = 4;
     p.swz = 0;
     const int wgs = (N + 127) / 128;
     const int units = (K + SPLIT_UNIT - 1) / SPLIT_UNIT;
@@ -915,7 +919,8 @@ GemmPlan plan_gemm_bf16(int M, int N, int K, bool force_single_split) {
             ctl = t;
         } else if (splits == 1 && wgs >= 128 && t > 5 && wide_wgs <= 256) {
             p.wide = 1;
-            p.nt = 2;
+            p.nt = 1;
+            p.nw = 8;
             p.mt = 5;
             ctl = 5;
         } else if (splits == 1 && wgs >= 512 && t > 5) {
@@ -923,7 +928,8 @@ GemmPlan plan_gemm_bf16(int M, int N, int K, bool force_single_split) {
             // dealt to the XCDs in super-tiles the passes of a column block run on one XCD at about the same
             // time and share the weights through its L2: 436 -> 402 us at 272 rows.
             p.wide = 1;
-            p.nt = 2;
+            p.nt = 1;
+            p.nw = 8;
             p.mt = 5;
             ctl = 5;
             p.swz = 4;
@@ -972,6 +978,8 @@ void launch_gemm_bf16(const bf16_t *a, const bf16_t *w, float *out, int M, int N
     if (M <= 32) {
         if (p.mt == 1) launch_small<1, 16>(a, w, out, M, N, K, p, out_row_major, st, ch);
         else launch_small<2, 8>(a, w, out, M, N, K, p, out_row_major, st, ch);
+    } else if (p.wide && p.nt == 1 && p.nw == 8) {     // eight waves side by side, one column tile each
+        launch_large<5, true, 1, 8>(a, w, out, M, N, K, p, out_row_major, st, ch);
     } else if (p.wide && p.nt == 1 && p.mt == 1) {
         launch_large<1, true, 1>(a, w, out, M, N, K, p, out_row_major, st, ch);
     } else if (p.wide && p.nt == 1 && p.mt == 2) {

@@ -162,7 +162,8 @@ struct GemmPlan {
     int splits;    // split-K factor
     int bk;        // K elements staged per LDS chunk
     int m_chunks;  // passes over M (grid.z)
-    int wide;      // 256-column workgroups (four waves side by side) instead of 128-column ones (2 x 2 waves)
+    int wide;      // the waves side by side, each over all row tiles of the pass (instead of 2 x 2 waves)
+    int nw;        // waves per workgroup: 4, or 8 (side by side, one column tile each: two waves per SIMD)
     int swz;       // > 0: (row pass, column block) plane dealt to the XCDs in super-tiles of swz x swz workgroups
 };
 
